@@ -1,0 +1,172 @@
+/*
+ * CPU oracle for optimizer update / update-undo and the state digest.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain scalar loops in IEEE binary64, written to be
+ * checked against the paper by eye.  Nothing here is tuned, blocked, fused or
+ * vectorised by hand, and nothing here is shared with (or included by) the GPU
+ * library.  Only the tests, the smoke check and the benchmark's CPU-baseline leg
+ * may call it.
+ *
+ * Conventions
+ *   - one call maps the state at iteration t ("old": x_t, m_{t-1}, v_{t-1}) to the
+ *     state at iteration t+1 ("new": x_{t+1}, m_t, v_t), or back;
+ *   - every array holds n doubles; outputs never alias inputs;
+ *   - `t` is the same integer in a step and in the undo of that step;
+ *   - no clamping, no flushing, NaN/Inf propagate as IEEE arithmetic dictates;
+ *   - build with -ffp-contract=off so that a*b+c is two roundings, as written.
+ *
+ * Readings of the paper taken here (the printed algorithms drift in their
+ * subscripts and two lines are garbled):
+ *   - weight-decay terms always use the pre-update parameter;
+ *   - Undo Adam's last line squares g' (the exponent is misprinted);
+ *   - Undo AdamW's parameter line has eps inside the denominator, (sqrt(v^)+eps),
+ *     the only placement that inverts the AdamW update line;
+ *   - AdamW's alpha, never defined in the paper, is 1;
+ *   - eps is added after the square root of the bias-corrected second moment;
+ *   - bias corrections are 1 - pow(beta, t), evaluated in binary64.
+ */
+#include <math.h>
+#include <stdint.h>
+
+/* ------------------------------------------------------------------------- */
+/* Alg. 1 (SGD with Momentum): m_t = mu m_{t-1} + (1-tau)(g_t + lambda x_t);    */
+/*                             x_{t+1} = x_t - eta_t m_t.                       */
+/* With mu = 0 this is App. A's plain SGD with the damped gradient kept in m.   */
+void oracle_sgdm_step(int64_t n, const double *x, const double *g, const double *m,
+                      double eta, double lambda, double mu, double tau,
+                      double *x_new, double *m_new)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double gp = g[i] + lambda * x[i];
+        double mt = mu * m[i] + (1.0 - tau) * gp;
+        m_new[i] = mt;
+        x_new[i] = x[i] - eta * mt;
+    }
+}
+
+/* Alg. 2 (Undo SGD with Momentum): x_t = x_{t+1} + eta_t m_t;                  */
+/*                                  m_{t-1} = (m_t - (1-tau)(g_t + lambda x_t))/mu. */
+/* The recovered x_t (not x_{t+1}) enters the weight-decay term.                 */
+/* mu = 0: the second line divides by zero; m_{t-1} carried no information into  */
+/* step t (it was multiplied by mu = 0), so the buffer is returned unchanged.    */
+void oracle_sgdm_undo(int64_t n, const double *x_new, const double *g, const double *m_new,
+                      double eta, double lambda, double mu, double tau,
+                      double *x_old, double *m_old)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double xt = x_new[i] + eta * m_new[i];
+        x_old[i] = xt;
+        if (mu == 0.0) {
+            m_old[i] = m_new[i];
+        } else {
+            double gp = g[i] + lambda * xt;
+            m_old[i] = (m_new[i] - (1.0 - tau) * gp) / mu;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* App. A, Alg. "Adam" (weight decay coupled into the gradient).                */
+void oracle_adam_step(int64_t n, const double *x, const double *g, const double *m, const double *v,
+                      double eta, double lambda, double beta1, double beta2, double eps, int64_t t,
+                      double *x_new, double *m_new, double *v_new)
+{
+    double bc1 = 1.0 - pow(beta1, (double)t);
+    double bc2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        double gp = g[i] + lambda * x[i];
+        double mt = beta1 * m[i] + (1.0 - beta1) * gp;
+        double vt = beta2 * v[i] + (1.0 - beta2) * (gp * gp);
+        double mhat = mt / bc1;
+        double vhat = vt / bc2;
+        m_new[i] = mt;
+        v_new[i] = vt;
+        x_new[i] = x[i] - eta * mhat / (sqrt(vhat) + eps);
+    }
+}
+
+/* App. A, Alg. "Undo Adam": the parameter is recovered first, from the new     */
+/* moments; the recovered parameter then rebuilds g'; the two moment recurrences */
+/* are solved for their previous values.                                         */
+void oracle_adam_undo(int64_t n, const double *x_new, const double *g, const double *m_new, const double *v_new,
+                      double eta, double lambda, double beta1, double beta2, double eps, int64_t t,
+                      double *x_old, double *m_old, double *v_old)
+{
+    double bc1 = 1.0 - pow(beta1, (double)t);
+    double bc2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        double mhat = m_new[i] / bc1;
+        double vhat = v_new[i] / bc2;
+        double xt = x_new[i] + eta * mhat / (sqrt(vhat) + eps);
+        double gp = g[i] + lambda * xt;
+        x_old[i] = xt;
+        m_old[i] = (m_new[i] - (1.0 - beta1) * gp) / beta1;
+        v_old[i] = (v_new[i] - (1.0 - beta2) * (gp * gp)) / beta2;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* App. A, Alg. "AdamW" (decoupled decay, alpha = 1): moments from the raw      */
+/* gradient; x_new = x - eta (u + lambda x), u = m^/(sqrt(v^)+eps).               */
+void oracle_adamw_step(int64_t n, const double *x, const double *g, const double *m, const double *v,
+                       double eta, double lambda, double beta1, double beta2, double eps, int64_t t,
+                       double *x_new, double *m_new, double *v_new)
+{
+    double bc1 = 1.0 - pow(beta1, (double)t);
+    double bc2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        double mt = beta1 * m[i] + (1.0 - beta1) * g[i];
+        double vt = beta2 * v[i] + (1.0 - beta2) * (g[i] * g[i]);
+        double mhat = mt / bc1;
+        double vhat = vt / bc2;
+        double u = mhat / (sqrt(vhat) + eps);
+        m_new[i] = mt;
+        v_new[i] = vt;
+        x_new[i] = x[i] - eta * (u + lambda * x[i]);
+    }
+}
+
+/* App. A, Alg. "Undo AdamW": x_old = (x_new + eta u)/(1 - eta lambda);          */
+/* moments as in Undo Adam but with the raw gradient.                            */
+void oracle_adamw_undo(int64_t n, const double *x_new, const double *g, const double *m_new, const double *v_new,
+                       double eta, double lambda, double beta1, double beta2, double eps, int64_t t,
+                       double *x_old, double *m_old, double *v_old)
+{
+    double bc1 = 1.0 - pow(beta1, (double)t);
+    double bc2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        double mhat = m_new[i] / bc1;
+        double vhat = v_new[i] / bc2;
+        double u = mhat / (sqrt(vhat) + eps);
+        x_old[i] = (x_new[i] + eta * u) / (1.0 - eta * lambda);
+        m_old[i] = (m_new[i] - (1.0 - beta1) * g[i]) / beta1;
+        v_old[i] = (v_new[i] - (1.0 - beta2) * (g[i] * g[i])) / beta2;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* State digest of one shard of n 32-bit words (n < 2^32).                       */
+/* Not from the paper (which keeps a per-parameter "updated" flag): it is this   */
+/* library's stand-in for that flag.  Each word is tagged with its index inside  */
+/* the shard, passed through a 64-bit mixer made of bijective steps, and the      */
+/* mixed words are summed modulo 2^64, so the order of summation is immaterial.   */
+/*   z = (i << 32) | w_i;  z += K1;  z ^= z >> 32;  z *= K2;  z ^= z >> 29;        */
+/*   z *= K3;  z ^= z >> 32;   digest = sum_i z   (empty shard: 0)                 */
+uint64_t oracle_digest(const uint32_t *w, int64_t n)
+{
+    const uint64_t K1 = 0x9E3779B97F4A7C15ull;
+    const uint64_t K2 = 0x6A09E667F3BCC909ull;
+    const uint64_t K3 = 0xBB67AE8584CAA73Bull;
+    uint64_t sum = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        uint64_t z = ((uint64_t)i << 32) | (uint64_t)w[i];
+        z += K1;
+        z ^= z >> 32;
+        z *= K2;
+        z ^= z >> 29;
+        z *= K3;
+        z ^= z >> 32;
+        sum += z;
+    }
+    return sum;
+}
