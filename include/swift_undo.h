@@ -1,0 +1,162 @@
+/*
+ * swift_undo.h -- C ABI of the update-undo library for one MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of Swift's replication-based recovery
+ * (arXiv 2302.06173, section "Update-undo"): a fused optimizer step over a list of tensors, the
+ * closed-form elementwise inverse of that step, which rolls the parameters and the optimizer
+ * moments of a replica back from iteration t+1 to iteration t using the cached gradient g_t, and a
+ * 64-bit digest of raw state bits that tells which tensors already hold the stepped state.
+ *
+ * General rules
+ *   - Plain C types only.  Every pointer is marked HOST or DEVICE below.  DEVICE pointers must
+ *     be ordinary device allocations of the GPU that is current (hipSetDevice) during the call.
+ *   - The caller owns every buffer it passes.  The library allocates only small internal tables
+ *     (tensor descriptors and chunk lists, cached per distinct tensor list), which it frees in
+ *     swift_shutdown() or when the process ends.
+ *   - HOST arrays (pointer arrays, numel, masks, hyper-parameters) are read during the call only.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t; NULL = the default stream) and the call
+ *     returns without waiting for it.  Order with respect to other work -- including update
+ *     kernels that were launched before a failure was noticed and must still run to completion
+ *     (paper, Implementation, "Update-undo") -- is stream order.
+ *   - Every entry point returns SWIFT_OK (0) or a negative swift_status.  On error nothing has
+ *     been enqueued and swift_last_error() describes the problem.  No exceptions, no aborts.
+ *   - theta, m and v are IEEE binary32; gradients are binary32 or bfloat16.  Arithmetic inside
+ *     the kernels is binary64 with one rounding to binary32 at each store.  NaN/Inf propagate;
+ *     denormals are kept; nothing is clamped.
+ *   - No two tensors of a list may overlap, and no other work may touch them while a call's
+ *     kernels run.
+ */
+#ifndef SWIFT_UNDO_H
+#define SWIFT_UNDO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SWIFT_OK = 0,
+  SWIFT_EINVAL = -1,         /* bad argument: null pointer, negative count, step < 1, unknown kind or
+                                dtype, non-finite or out-of-range hyper-parameter, missing v array,
+                                pointer that is not device memory of the current GPU or whose
+                                allocation is shorter than numel elements, misaligned pointer */
+  SWIFT_ENOTINVERTIBLE = -2, /* undo only: the inverse divides by zero (beta1 = 0, beta2 = 0, or
+                                eta*lambda = 1 for AdamW) */
+  SWIFT_EHIP = -3            /* a HIP runtime call failed; the message carries its error name */
+} swift_status;
+
+typedef enum {
+  SWIFT_SGDM = 0,  /* Alg. 1 / Alg. 2: SGD with momentum mu, dampening tau, coupled decay lambda.
+                      mu = 0 is App. A's plain SGD with the damped gradient left in the m buffer. */
+  SWIFT_ADAM = 1,  /* App. A "Adam" / "Undo Adam": decay coupled into the gradient, g' = g + lambda x */
+  SWIFT_ADAMW = 2  /* App. A "AdamW" / "Undo AdamW": decoupled decay, alpha = 1 */
+} swift_opt_kind;
+
+typedef enum { SWIFT_F32 = 0, SWIFT_BF16 = 1 } swift_dtype; /* gradients only */
+
+/* Hyper-parameters in the paper's notation (Alg. 1, Alg. 2, App. A).  `step` is the t of m_t and
+ * of the bias corrections 1 - beta^t; a step and the undo of that step use the same value. */
+typedef struct {
+  int32_t kind;         /* swift_opt_kind */
+  int32_t grad_dtype;   /* swift_dtype */
+  int64_t step;         /* t >= 1 */
+  double lr;            /* eta_t, finite */
+  double weight_decay;  /* lambda >= 0 */
+  double momentum;      /* mu in [0, 1]   (SGDM) */
+  double dampening;     /* tau in [0, 1]  (SGDM) */
+  double beta1, beta2;  /* in [0, 1)      (Adam, AdamW) */
+  double eps;           /* >= 0           (Adam, AdamW) */
+} swift_hparams;
+
+/* A list of n tensors.  All five arrays are HOST arrays of length n; the pointers they hold are
+ * DEVICE pointers to contiguous 1-D storage of numel[i] elements.  param, m, v: binary32,
+ * 4-byte aligned, updated in place.  grad: binary32 (4-byte aligned) or bfloat16 (2-byte
+ * aligned), NEVER written -- the undo needs it intact (paper, "Update-undo": only the latest
+ * gradient is cached, no extra memory).  16-byte alignment of all of a tensor's pointers
+ * (8-byte for bf16 gradients) selects the 128-bit access path; results are bit-identical either way.
+ * v may be NULL for SWIFT_SGDM.  Tensors with numel 0 are allowed and skipped. */
+typedef struct {
+  int64_t n;
+  void *const *param;
+  const void *const *grad;
+  void *const *m;
+  void *const *v;
+  const int64_t *numel;
+} swift_tensor_list;
+
+/* Optimizer step t: (x_t, g_t, m_{t-1}, v_{t-1}) -> (x_{t+1}, m_t, v_t) in place, for every
+ * tensor whose mask entry is non-zero (all tensors if the mask is NULL).
+ *   SGDM  (Alg. 1):          g' = g + lambda x;  m <- mu m + (1-tau) g';  x <- x - eta m
+ *   Adam  (App. A "Adam"):   g' = g + lambda x;  m <- beta1 m + (1-beta1) g';
+ *                            v <- beta2 v + (1-beta2) g'^2;
+ *                            x <- x - eta (m/(1-beta1^t)) / (sqrt(v/(1-beta2^t)) + eps)
+ *   AdamW (App. A "AdamW"):  moments from the raw g;  x <- x - eta (u + lambda x), u as above.
+ * host_mask: HOST, n bytes, nullable. */
+int swift_opt_step(const swift_tensor_list *list, const swift_hparams *hp,
+                   const uint8_t *host_mask, void *hip_stream);
+
+/* Undo of step t: (x_{t+1}, g_t, m_t, v_t) -> (x_t, m_{t-1}, v_{t-1}) in place, for every tensor
+ * marked as updated (mask entry non-zero; all if NULL).  The parameter is recovered first, from
+ * the new moments; coupled decay is rebuilt from the recovered parameter.
+ *   SGDM  (Alg. 2):              x <- x + eta m;  m <- (m - (1-tau)(g + lambda x)) / mu
+ *                                (mu = 0: the m buffer is left as it is)
+ *   Adam  (App. A "Undo Adam"):  x <- x + eta u;  g' = g + lambda x;
+ *                                m <- (m - (1-beta1) g')/beta1;  v <- (v - (1-beta2) g'^2)/beta2
+ *   AdamW (App. A "Undo AdamW"): x <- (x + eta u)/(1 - eta lambda);  m, v as Adam with raw g.
+ * Because the step rounds to binary32, the result equals the pre-step state only up to
+ * floating-point error (paper, "Update-undo"); it matches a binary64 evaluation of the same
+ * formulas on the same input bits to within binary32 rounding.
+ * Returns SWIFT_ENOTINVERTIBLE as described at swift_status. */
+int swift_opt_undo(const swift_tensor_list *list, const swift_hparams *hp,
+                   const uint8_t *host_mask, void *hip_stream);
+
+/* The same two operations with the "updated" marks in DEVICE memory (n bytes, not nullable), read
+ * by the kernel when it runs: the mask can be produced by swift_mask_from_digests on the same
+ * stream with no host round trip. */
+int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
+                         const uint8_t *device_mask, void *hip_stream);
+int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp,
+                         const uint8_t *device_mask, void *hip_stream);
+
+/* 64-bit digests of raw 32-bit words.  This stands in for the paper's per-parameter "marked as
+ * updated" flag (Implementation, "Update-undo"): a shard whose digest differs from the digest
+ * recorded at iteration t holds stepped bits.  For a shard of words w_0..w_{k-1} (k < 2^32), with
+ * i the index inside the shard and all arithmetic modulo 2^64:
+ *   z = (i << 32) | w_i;  z += K1;  z ^= z >> 32;  z *= K2;  z ^= z >> 29;  z *= K3;  z ^= z >> 32
+ *   digest = sum_i z                       (empty shard: 0)
+ *   K1 = 0x9E3779B97F4A7C15, K2 = 0x6A09E667F3BCC909, K3 = 0xBB67AE8584CAA73B
+ * buf: HOST array of n_buf DEVICE pointers to 4-byte elements (4-byte aligned); numel: HOST.
+ * shard_elems = 0: one shard per buffer (numel < 2^32 required); otherwise 0 < shard_elems < 2^32
+ * and a buffer is cut into consecutive shards of that many words, the last one short.
+ * out_device: DEVICE, swift_digest_count(...) entries, buffer-major; fully overwritten. */
+int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *numel,
+                       int64_t shard_elems, uint64_t *out_device, void *hip_stream);
+
+/* Number of digests swift_state_digest writes: sum_i ceil(numel_i / shard_elems), or n_buf when
+ * shard_elems = 0.  Pure host arithmetic.  Returns a negative swift_status on bad arguments. */
+int64_t swift_digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems);
+
+/* Selective undo: derive the per-tensor "updated" marks from two digest arrays.  Both arrays are
+ * DEVICE arrays of n_groups * n_tensors digests laid out group-major (e.g. the per-tensor digests
+ * of all theta, then all m, then all v, as swift_state_digest writes them for that buffer order
+ * with shard_elems = 0).  mask_device[i] = 1 if any group's digest of tensor i differs, else 0.
+ * mask_device: DEVICE, n_tensors bytes, fully overwritten. */
+int swift_mask_from_digests(int64_t n_tensors, int64_t n_groups, const uint64_t *before_device,
+                            const uint64_t *after_device, uint8_t *mask_device, void *hip_stream);
+
+/* Measurement aid: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers
+ * 16-byte aligned, DEVICE) written with the same access pattern as the optimizer kernels.  It
+ * gives the practical HBM ceiling of this access pattern and calibrates profiler byte counters. */
+int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, void *hip_stream);
+
+/* Frees every cached table on every device (synchronises those devices first). */
+int swift_shutdown(void);
+
+/* Message of the last error on the calling thread ("" if none).  HOST, owned by the library. */
+const char *swift_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWIFT_UNDO_H */

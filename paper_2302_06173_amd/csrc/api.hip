@@ -1,0 +1,591 @@
+// Host side of the C ABI declared in swift_undo.h: argument validation, derived scalars in
+// binary64, the planner that turns a tensor list into a device-resident chunk table (cached per
+// distinct list), and the kernel launches.  One translation unit, built with hipcc for gfx950.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <list>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "swift_undo.h"
+#include "opt_kernels.hpp"
+#include "digest_kernels.hpp"
+
+namespace swift {
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+#define SWIFT_HIP(call)                                                                       \
+  do {                                                                                        \
+    hipError_t e_ = (call);                                                                   \
+    if (e_ != hipSuccess)                                                                     \
+      return fail(SWIFT_EHIP, "%s failed: %s (%s)", #call, hipGetErrorName(e_), hipGetErrorString(e_)); \
+  } while (0)
+
+long env_long(const char *name, long dflt) {
+  const char *s = getenv(name);
+  if (!s || !*s) return dflt;
+  char *end = nullptr;
+  long v = strtol(s, &end, 10);
+  return (end && *end == 0) ? v : dflt;
+}
+
+// ------------------------------------------------------------------------------------------
+// Device facts, queried once per device.
+struct DeviceInfo {
+  int cus = 0;
+};
+
+int device_info(int dev, DeviceInfo *out) {
+  static std::mutex mu;
+  static std::vector<DeviceInfo> cache;
+  std::lock_guard<std::mutex> lock(mu);
+  if ((int)cache.size() <= dev) cache.resize(dev + 1);
+  if (cache[dev].cus == 0) {
+    int cus = 0;
+    SWIFT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus <= 0) return fail(SWIFT_EHIP, "device %d reports %d compute units", dev, cus);
+    cache[dev].cus = cus;
+  }
+  *out = cache[dev];
+  return SWIFT_OK;
+}
+
+// Resident workgroups per compute unit for `kernel`, from the runtime's occupancy calculator.
+int resident_groups(const void *kernel, int *out) {
+  int nb = 0;
+  SWIFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kThreads, 0));
+  long forced = env_long("SWIFT_WG_PER_CU", 0);      // tuning knob for sweeps
+  if (forced > 0 && forced <= 64) nb = (int)forced;
+  *out = nb < 1 ? 1 : nb;
+  return SWIFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Plans: descriptor table + chunk table in one device allocation, cached by the exact
+// contents of the host arrays that produced them.
+struct Plan {
+  std::string key;
+  int device = -1;
+  void *dev_mem = nullptr;       // [descs | chunks]
+  size_t desc_bytes = 0;
+  uint32_t n_chunks = 0;
+  uint32_t chunk_elems = 0;
+  uint64_t n_out = 0;            // digest plans: number of outputs
+  const void *descs() const { return dev_mem; }
+  const ChunkRef *chunks() const {
+    return reinterpret_cast<const ChunkRef *>(static_cast<const char *>(dev_mem) + desc_bytes);
+  }
+  ~Plan() {
+    if (dev_mem) {
+      int cur = -1;
+      if (hipGetDevice(&cur) == hipSuccess && cur != device) (void)hipSetDevice(device);
+      (void)hipFree(dev_mem);    // synchronises the device: no kernel still reads the table
+      if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
+    }
+  }
+};
+
+constexpr size_t kMaxPlans = 32;
+std::mutex g_plan_mu;
+std::list<std::shared_ptr<Plan>> *g_plans = nullptr;   // most recently used first; leaked at exit on purpose
+
+std::shared_ptr<Plan> find_plan(const std::string &key) {
+  std::lock_guard<std::mutex> lock(g_plan_mu);
+  if (!g_plans) g_plans = new std::list<std::shared_ptr<Plan>>();
+  for (auto it = g_plans->begin(); it != g_plans->end(); ++it) {
+    if ((*it)->key == key) {
+      auto p = *it;
+      g_plans->erase(it);
+      g_plans->push_front(p);
+      return p;
+    }
+  }
+  return nullptr;
+}
+
+void keep_plan(const std::shared_ptr<Plan> &p) {
+  std::shared_ptr<Plan> dropped;   // destroyed (hipFree) outside the lock
+  std::lock_guard<std::mutex> lock(g_plan_mu);
+  if (!g_plans) g_plans = new std::list<std::shared_ptr<Plan>>();
+  g_plans->push_front(p);
+  if (g_plans->size() > kMaxPlans) {
+    dropped = g_plans->back();
+    g_plans->pop_back();
+  }
+}
+
+template <typename T>
+void key_add(std::string &k, const T &v) { k.append(reinterpret_cast<const char *>(&v), sizeof v); }
+
+// A device range [p, p + bytes) must lie inside one allocation of the current device.
+int check_device_range(const void *p, size_t bytes, int dev, const char *what, int64_t idx) {
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, p);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(SWIFT_EINVAL, "%s[%lld] = %p is not known to the HIP runtime (%s)", what, (long long)idx, p,
+                hipGetErrorName(e));
+  }
+  if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
+    return fail(SWIFT_EINVAL, "%s[%lld] = %p is not device memory", what, (long long)idx, p);
+  if (attr.type == hipMemoryTypeDevice && attr.device != dev)
+    return fail(SWIFT_EINVAL, "%s[%lld] = %p lives on device %d, current device is %d", what, (long long)idx, p,
+                attr.device, dev);
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  e = hipMemGetAddressRange(&base, &size, const_cast<void *>(p));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(SWIFT_EINVAL, "%s[%lld] = %p: cannot find its allocation (%s)", what, (long long)idx, p,
+                hipGetErrorName(e));
+  }
+  const char *b = static_cast<const char *>(base), *q = static_cast<const char *>(p);
+  if (q < b || q + bytes > b + size)
+    return fail(SWIFT_EINVAL, "%s[%lld]: %zu bytes at %p run past the end of its allocation (%zu bytes at %p)", what,
+                (long long)idx, bytes, p, size, base);
+  return SWIFT_OK;
+}
+
+uint32_t pick_chunk_elems(uint64_t total, uint64_t resident_wgs, int unroll) {
+  const uint32_t tile = (uint32_t)unroll * kThreads * 4;       // elements per unrolled workgroup pass
+  long forced = env_long("SWIFT_CHUNK_ELEMS", 0);              // tuning knob for sweeps
+  if (forced >= (long)tile && forced <= (1l << 22) && forced % tile == 0) return (uint32_t)forced;
+  uint32_t ce = 16384;
+  while (ce > 4096 && total / ce < 8 * resident_wgs) ce >>= 1;
+  if (ce < tile) ce = tile;
+  return ce;
+}
+
+int upload_plan(Plan &plan, const void *descs, size_t desc_bytes, const std::vector<ChunkRef> &chunks) {
+  plan.desc_bytes = (desc_bytes + 255) & ~size_t(255);
+  const size_t total = plan.desc_bytes + std::max<size_t>(chunks.size(), 1) * sizeof(ChunkRef);
+  SWIFT_HIP(hipMalloc(&plan.dev_mem, total));
+  // Synchronous copies: when they return the table is complete in device memory, so any stream
+  // may read it.  This happens once per distinct tensor list.
+  if (desc_bytes) SWIFT_HIP(hipMemcpy(plan.dev_mem, descs, desc_bytes, hipMemcpyHostToDevice));
+  if (!chunks.empty())
+    SWIFT_HIP(hipMemcpy(static_cast<char *>(plan.dev_mem) + plan.desc_bytes, chunks.data(),
+                        chunks.size() * sizeof(ChunkRef), hipMemcpyHostToDevice));
+  plan.n_chunks = (uint32_t)chunks.size();
+  return SWIFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Optimizer calls.
+struct Interval {
+  uintptr_t lo, hi;
+  bool written;
+};
+
+int validate_hparams(const swift_hparams *hp, bool undo, OptConsts *c) {
+  if (!hp) return fail(SWIFT_EINVAL, "hparams is NULL");
+  if (hp->kind < SWIFT_SGDM || hp->kind > SWIFT_ADAMW) return fail(SWIFT_EINVAL, "unknown optimizer kind %d", hp->kind);
+  if (hp->grad_dtype != SWIFT_F32 && hp->grad_dtype != SWIFT_BF16)
+    return fail(SWIFT_EINVAL, "unknown gradient dtype %d", hp->grad_dtype);
+  if (hp->step < 1) return fail(SWIFT_EINVAL, "step must be >= 1 (got %lld)", (long long)hp->step);
+  if (!std::isfinite(hp->lr)) return fail(SWIFT_EINVAL, "lr is not finite");
+  if (!std::isfinite(hp->weight_decay) || hp->weight_decay < 0) return fail(SWIFT_EINVAL, "weight_decay must be finite and >= 0");
+  memset(c, 0, sizeof *c);
+  c->eta = hp->lr;
+  c->lam = hp->weight_decay;
+  if (hp->kind == SWIFT_SGDM) {
+    if (!(hp->momentum >= 0 && hp->momentum <= 1)) return fail(SWIFT_EINVAL, "momentum must be in [0, 1]");
+    if (!(hp->dampening >= 0 && hp->dampening <= 1)) return fail(SWIFT_EINVAL, "dampening must be in [0, 1]");
+    c->mu = hp->momentum;
+    c->omt = 1.0 - hp->dampening;
+    c->mu_is_zero = (hp->momentum == 0.0);
+    c->inv_mu = c->mu_is_zero ? 0.0 : 1.0 / hp->momentum;
+    return SWIFT_OK;
+  }
+  if (!(hp->beta1 >= 0 && hp->beta1 < 1) || !(hp->beta2 >= 0 && hp->beta2 < 1))
+    return fail(SWIFT_EINVAL, "beta1 and beta2 must be in [0, 1)");
+  if (!std::isfinite(hp->eps) || hp->eps < 0) return fail(SWIFT_EINVAL, "eps must be finite and >= 0");
+  const double oml = 1.0 - hp->lr * hp->weight_decay;
+  if (undo) {
+    if (hp->beta1 == 0 || hp->beta2 == 0)
+      return fail(SWIFT_ENOTINVERTIBLE, "undo divides by beta: beta1 = %g, beta2 = %g", hp->beta1, hp->beta2);
+    if (hp->kind == SWIFT_ADAMW && oml == 0)
+      return fail(SWIFT_ENOTINVERTIBLE, "undo divides by 1 - lr*weight_decay = 0");
+  }
+  c->b1 = hp->beta1;
+  c->b2 = hp->beta2;
+  c->c1 = 1.0 - hp->beta1;
+  c->c2 = 1.0 - hp->beta2;
+  c->inv_b1 = hp->beta1 != 0 ? 1.0 / hp->beta1 : 0.0;
+  c->inv_b2 = hp->beta2 != 0 ? 1.0 / hp->beta2 : 0.0;
+  c->rbc1 = 1.0 / (1.0 - std::pow(hp->beta1, (double)hp->step));   // t >= 1 and beta < 1: never 1/0
+  c->rbc2 = 1.0 / (1.0 - std::pow(hp->beta2, (double)hp->step));
+  c->eps = hp->eps;
+  c->inv_oml = oml != 0 ? 1.0 / oml : 0.0;
+  return SWIFT_OK;
+}
+
+int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
+  if (!l) return fail(SWIFT_EINVAL, "tensor list is NULL");
+  if (l->n < 0 || l->n > (int64_t)0x7fffffff) return fail(SWIFT_EINVAL, "tensor count %lld out of range", (long long)l->n);
+  if (l->n == 0) return SWIFT_OK;
+  if (!l->param || !l->grad || !l->m || !l->numel) return fail(SWIFT_EINVAL, "param, grad, m and numel arrays must not be NULL");
+  const bool hasv = hp->kind != SWIFT_SGDM;
+  if (hasv && !l->v) return fail(SWIFT_EINVAL, "Adam/AdamW need the v array");
+  const uintptr_t galign = hp->grad_dtype == SWIFT_BF16 ? 1 : 3;
+  for (int64_t i = 0; i < l->n; ++i) {
+    if (l->numel[i] < 0) return fail(SWIFT_EINVAL, "numel[%lld] is negative", (long long)i);
+    if (l->numel[i] == 0) continue;
+    if (!l->param[i] || !l->grad[i] || !l->m[i] || (hasv && !l->v[i]))
+      return fail(SWIFT_EINVAL, "tensor %lld has a NULL pointer", (long long)i);
+    if (((uintptr_t)l->param[i] & 3) || ((uintptr_t)l->m[i] & 3) || (hasv && ((uintptr_t)l->v[i] & 3)) ||
+        ((uintptr_t)l->grad[i] & galign))
+      return fail(SWIFT_EINVAL, "tensor %lld has a pointer that is not aligned to its element size", (long long)i);
+  }
+  return SWIFT_OK;
+}
+
+int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, int dev,
+                   uint64_t resident_wgs, std::shared_ptr<Plan> *out) {
+  const bool hasv = hp->kind != SWIFT_SGDM;
+  const bool bf16 = hp->grad_dtype == SWIFT_BF16;
+  std::string key;
+  key.reserve(64 + (size_t)l->n * 41);
+  key_add(key, (uint8_t)'O');
+  key_add(key, dev);
+  key_add(key, (uint8_t)hasv);
+  key_add(key, (uint8_t)bf16);
+  key_add(key, l->n);
+  key_add(key, env_long("SWIFT_CHUNK_ELEMS", 0));
+  for (int64_t i = 0; i < l->n; ++i) {
+    const uint8_t on = host_mask ? (host_mask[i] != 0) : 1;
+    key_add(key, l->numel[i]);
+    key_add(key, on);
+    if (l->numel[i] == 0) continue;
+    key_add(key, l->param[i]);
+    key_add(key, l->grad[i]);
+    key_add(key, l->m[i]);
+    if (hasv) key_add(key, l->v[i]);
+  }
+  if (auto hit = find_plan(key)) {
+    *out = hit;
+    return SWIFT_OK;
+  }
+
+  // Miss: check every pointer against the runtime's allocation records, check that nothing that
+  // is written overlaps anything else, then build and upload the tables.
+  std::vector<TensorDesc> descs((size_t)l->n);
+  std::vector<Interval> iv;
+  iv.reserve((size_t)l->n * 4);
+  uint64_t total = 0;
+  const size_t gsz = bf16 ? 2 : 4;
+  for (int64_t i = 0; i < l->n; ++i) {
+    TensorDesc &d = descs[(size_t)i];
+    memset(&d, 0, sizeof d);
+    const uint64_t n = (uint64_t)l->numel[i];
+    if (n == 0) continue;
+    int rc;
+    if ((rc = check_device_range(l->param[i], n * 4, dev, "param", i))) return rc;
+    if ((rc = check_device_range(l->grad[i], n * gsz, dev, "grad", i))) return rc;
+    if ((rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
+    if (hasv && (rc = check_device_range(l->v[i], n * 4, dev, "v", i))) return rc;
+    d.x = static_cast<float *>(l->param[i]);
+    d.g = l->grad[i];
+    d.m = static_cast<float *>(l->m[i]);
+    d.v = hasv ? static_cast<float *>(l->v[i]) : nullptr;
+    d.numel = (int64_t)n;
+    uintptr_t bits = (uintptr_t)d.x | (uintptr_t)d.m | (hasv ? (uintptr_t)d.v : 0);
+    d.vec_ok = ((bits & 15) == 0) && (((uintptr_t)d.g & (bf16 ? 7 : 15)) == 0);
+    iv.push_back({(uintptr_t)d.x, (uintptr_t)d.x + n * 4, true});
+    iv.push_back({(uintptr_t)d.g, (uintptr_t)d.g + n * gsz, false});
+    iv.push_back({(uintptr_t)d.m, (uintptr_t)d.m + n * 4, true});
+    if (hasv) iv.push_back({(uintptr_t)d.v, (uintptr_t)d.v + n * 4, true});
+    if (!host_mask || host_mask[i]) total += n;
+  }
+  std::sort(iv.begin(), iv.end(), [](const Interval &a, const Interval &b) { return a.lo < b.lo; });
+  for (size_t k = 1; k < iv.size(); ++k)
+    if (iv[k].lo < iv[k - 1].hi && (iv[k].written || iv[k - 1].written))
+      return fail(SWIFT_EINVAL, "buffers overlap: [%p, %p) and [%p, %p)", (void *)iv[k - 1].lo, (void *)iv[k - 1].hi,
+                  (void *)iv[k].lo, (void *)iv[k].hi);
+
+  auto plan = std::make_shared<Plan>();
+  plan->key = std::move(key);
+  plan->device = dev;
+  plan->chunk_elems = pick_chunk_elems(total, resident_wgs, SWIFT_UNROLL);
+  std::vector<ChunkRef> chunks;
+  chunks.reserve((size_t)(total / plan->chunk_elems) + (size_t)l->n);
+  for (int64_t i = 0; i < l->n; ++i) {
+    if (host_mask && !host_mask[i]) continue;
+    const uint64_t n = (uint64_t)l->numel[i];
+    const uint64_t nc = (n + plan->chunk_elems - 1) / plan->chunk_elems;
+    if (nc > 0xffffffffull) return fail(SWIFT_EINVAL, "tensor %lld is too large", (long long)i);
+    for (uint64_t k = 0; k < nc; ++k) chunks.push_back({(uint32_t)i, (uint32_t)k});
+  }
+  if (chunks.size() > 0xffffffffull) return fail(SWIFT_EINVAL, "tensor list is too large");
+  int rc = upload_plan(*plan, descs.data(), descs.size() * sizeof(TensorDesc), chunks);
+  if (rc) return rc;
+  keep_plan(plan);
+  *out = plan;
+  return SWIFT_OK;
+}
+
+typedef void (*OptKernel)(const TensorDesc *, const ChunkRef *, uint32_t, uint32_t, const uint8_t *, const OptConsts);
+
+template <int KIND, bool UNDO>
+OptKernel pick_grad(bool bf16) {
+  return bf16 ? opt_kernel<KIND, UNDO, true, SWIFT_NT != 0, SWIFT_UNROLL>
+              : opt_kernel<KIND, UNDO, false, SWIFT_NT != 0, SWIFT_UNROLL>;
+}
+
+OptKernel pick_kernel(int kind, bool undo, bool bf16) {
+  switch (kind) {
+    case SWIFT_SGDM: return undo ? pick_grad<kSGDM, true>(bf16) : pick_grad<kSGDM, false>(bf16);
+    case SWIFT_ADAM: return undo ? pick_grad<kADAM, true>(bf16) : pick_grad<kADAM, false>(bf16);
+    default: return undo ? pick_grad<kADAMW, true>(bf16) : pick_grad<kADAMW, false>(bf16);
+  }
+}
+
+int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask,
+             const uint8_t *device_mask, bool want_dmask, bool undo, void *stream) {
+  OptConsts c;
+  int rc = validate_hparams(hp, undo, &c);
+  if (rc) return rc;
+  if ((rc = validate_list(l, hp))) return rc;
+  if (want_dmask && !device_mask && l->n > 0) return fail(SWIFT_EINVAL, "device mask is NULL");
+  if (l->n == 0) return SWIFT_OK;
+  int dev = -1;
+  SWIFT_HIP(hipGetDevice(&dev));
+  DeviceInfo info;
+  if ((rc = device_info(dev, &info))) return rc;
+  const OptKernel kernel = pick_kernel(hp->kind, undo, hp->grad_dtype == SWIFT_BF16);
+  int per_cu = 1;
+  if ((rc = resident_groups(reinterpret_cast<const void *>(kernel), &per_cu))) return rc;
+  const uint64_t resident = (uint64_t)info.cus * (uint64_t)per_cu;
+  if (want_dmask && (rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
+  std::shared_ptr<Plan> plan;
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, resident, &plan))) return rc;
+  if (plan->n_chunks == 0) return SWIFT_OK;
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(plan->n_chunks, resident);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const TensorDesc *>(plan->descs()), plan->chunks(), plan->n_chunks, plan->chunk_elems,
+                     device_mask, c);
+  SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Digest.
+int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, bool set_error) {
+  if (n_buf < 0 || (n_buf > 0 && !numel) || shard_elems < 0 || shard_elems >= (int64_t)1 << 32)
+    return set_error ? fail(SWIFT_EINVAL, "digest: bad n_buf, numel or shard_elems") : SWIFT_EINVAL;
+  int64_t total = 0;
+  for (int64_t i = 0; i < n_buf; ++i) {
+    if (numel[i] < 0) return set_error ? fail(SWIFT_EINVAL, "digest: numel[%lld] is negative", (long long)i) : SWIFT_EINVAL;
+    if (shard_elems == 0) {
+      if (numel[i] >= (int64_t)1 << 32)
+        return set_error ? fail(SWIFT_EINVAL, "digest: buffer %lld has 2^32 words or more; give shard_elems", (long long)i)
+                         : SWIFT_EINVAL;
+      total += 1;
+    } else {
+      total += (numel[i] + shard_elems - 1) / shard_elems;
+    }
+  }
+  return total;
+}
+
+int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *numel, int64_t shard_elems, int dev,
+                      uint64_t resident_wgs, std::shared_ptr<Plan> *out) {
+  std::string key;
+  key.reserve(64 + (size_t)n_buf * 16);
+  key_add(key, (uint8_t)'D');
+  key_add(key, dev);
+  key_add(key, n_buf);
+  key_add(key, shard_elems);
+  key_add(key, env_long("SWIFT_CHUNK_ELEMS", 0));
+  for (int64_t i = 0; i < n_buf; ++i) {
+    key_add(key, numel[i]);
+    key_add(key, buf[i]);
+  }
+  if (auto hit = find_plan(key)) {
+    *out = hit;
+    return SWIFT_OK;
+  }
+  std::vector<DigestDesc> descs((size_t)n_buf);
+  uint64_t total = 0, n_out = 0;
+  for (int64_t i = 0; i < n_buf; ++i) {
+    const uint64_t n = (uint64_t)numel[i];
+    descs[(size_t)i] = {static_cast<const uint32_t *>(buf[i]), (int64_t)n, n_out};
+    n_out += shard_elems ? (n + shard_elems - 1) / shard_elems : 1;
+    if (n == 0) continue;
+    if (!buf[i]) return fail(SWIFT_EINVAL, "digest: buffer %lld is NULL", (long long)i);
+    if ((uintptr_t)buf[i] & 3) return fail(SWIFT_EINVAL, "digest: buffer %lld is not 4-byte aligned", (long long)i);
+    int rc = check_device_range(buf[i], n * 4, dev, "buf", i);
+    if (rc) return rc;
+    total += n;
+  }
+  auto plan = std::make_shared<Plan>();
+  plan->key = std::move(key);
+  plan->device = dev;
+  plan->n_out = n_out;
+  plan->chunk_elems = pick_chunk_elems(total, resident_wgs, SWIFT_UNROLL);
+  const uint64_t ce = plan->chunk_elems;
+  std::vector<ChunkRef> chunks;
+  chunks.reserve((size_t)(total / ce) + (size_t)n_out);
+  for (int64_t i = 0; i < n_buf; ++i) {
+    const uint64_t n = (uint64_t)numel[i];
+    if (n == 0) continue;
+    const uint64_t S = shard_elems ? (uint64_t)shard_elems : n;
+    const uint64_t cps = (S + ce - 1) / ce;                 // chunk numbers per full shard
+    const uint64_t n_shards = (n + S - 1) / S;
+    if (cps * n_shards > 0xffffffffull) return fail(SWIFT_EINVAL, "digest: buffer %lld needs too many chunks", (long long)i);
+    for (uint64_t s = 0; s < n_shards; ++s) {
+      const uint64_t shard_len = std::min<uint64_t>(S, n - s * S);
+      const uint64_t nc = (shard_len + ce - 1) / ce;
+      for (uint64_t k = 0; k < nc; ++k) chunks.push_back({(uint32_t)i, (uint32_t)(s * cps + k)});
+    }
+  }
+  if (chunks.size() > 0xffffffffull) return fail(SWIFT_EINVAL, "digest: too many chunks");
+  int rc = upload_plan(*plan, descs.data(), descs.size() * sizeof(DigestDesc), chunks);
+  if (rc) return rc;
+  keep_plan(plan);
+  *out = plan;
+  return SWIFT_OK;
+}
+
+}  // namespace
+}  // namespace swift
+
+using namespace swift;
+
+extern "C" {
+
+int swift_opt_step(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask, void *hip_stream) {
+  return opt_call(list, hp, host_mask, nullptr, false, false, hip_stream);
+}
+
+int swift_opt_undo(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask, void *hip_stream) {
+  return opt_call(list, hp, host_mask, nullptr, false, true, hip_stream);
+}
+
+int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
+                         void *hip_stream) {
+  return opt_call(list, hp, nullptr, device_mask, true, false, hip_stream);
+}
+
+int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
+                         void *hip_stream) {
+  return opt_call(list, hp, nullptr, device_mask, true, true, hip_stream);
+}
+
+int64_t swift_digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems) {
+  return digest_count(n_buf, numel, shard_elems, true);
+}
+
+int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *numel, int64_t shard_elems,
+                       uint64_t *out_device, void *hip_stream) {
+  const int64_t n_out = digest_count(n_buf, numel, shard_elems, true);
+  if (n_out < 0) return (int)n_out;
+  if (n_buf > 0 && !buf) return fail(SWIFT_EINVAL, "digest: buf array is NULL");
+  if (n_out == 0) return SWIFT_OK;
+  if (!out_device) return fail(SWIFT_EINVAL, "digest: out_device is NULL");
+  if ((uintptr_t)out_device & 7) return fail(SWIFT_EINVAL, "digest: out_device is not 8-byte aligned");
+  int dev = -1, rc;
+  SWIFT_HIP(hipGetDevice(&dev));
+  DeviceInfo info;
+  if ((rc = device_info(dev, &info))) return rc;
+  if ((rc = check_device_range(out_device, (size_t)n_out * 8, dev, "out_device", 0))) return rc;
+  const auto kernel = digest_kernel<SWIFT_NT != 0, SWIFT_UNROLL>;
+  int per_cu = 1;
+  if ((rc = resident_groups(reinterpret_cast<const void *>(kernel), &per_cu))) return rc;
+  const uint64_t resident = (uint64_t)info.cus * (uint64_t)per_cu;
+  std::shared_ptr<Plan> plan;
+  if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, resident, &plan))) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // The output is cleared by a kernel (not a memset node) so that the call can be captured in a graph.
+  const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(fill_grid), dim3(kThreads), 0, stream, out_device, (uint64_t)n_out,
+                     (uint64_t)0);
+  SWIFT_HIP(hipGetLastError());
+  if (plan->n_chunks == 0) return SWIFT_OK;
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(plan->n_chunks, resident);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
+                     plan->chunks(), plan->n_chunks, plan->chunk_elems, (uint64_t)shard_elems,
+                     reinterpret_cast<unsigned long long *>(out_device));
+  SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+int swift_mask_from_digests(int64_t n_tensors, int64_t n_groups, const uint64_t *before_device,
+                            const uint64_t *after_device, uint8_t *mask_device, void *hip_stream) {
+  if (n_tensors < 0 || n_tensors > (int64_t)0x7fffffff || n_groups < 1 || n_groups > 64)
+    return fail(SWIFT_EINVAL, "mask_from_digests: n_tensors or n_groups out of range");
+  if (n_tensors == 0) return SWIFT_OK;
+  if (!before_device || !after_device || !mask_device) return fail(SWIFT_EINVAL, "mask_from_digests: NULL pointer");
+  if (((uintptr_t)before_device | (uintptr_t)after_device) & 7)
+    return fail(SWIFT_EINVAL, "mask_from_digests: digest arrays are not 8-byte aligned");
+  int dev = -1, rc;
+  SWIFT_HIP(hipGetDevice(&dev));
+  const size_t dbytes = (size_t)n_tensors * (size_t)n_groups * 8;
+  if ((rc = check_device_range(before_device, dbytes, dev, "before_device", 0))) return rc;
+  if ((rc = check_device_range(after_device, dbytes, dev, "after_device", 0))) return rc;
+  if ((rc = check_device_range(mask_device, (size_t)n_tensors, dev, "mask_device", 0))) return rc;
+  const uint32_t grid = (uint32_t)std::min<int64_t>((n_tensors + kThreads - 1) / kThreads, 1024);
+  hipLaunchKernelGGL(mask_from_digests_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                     (uint32_t)n_tensors, (uint32_t)n_groups, before_device, after_device, mask_device);
+  SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, void *hip_stream) {
+  if (bytes < 0 || (bytes & 15)) return fail(SWIFT_EINVAL, "stream_copy: bytes must be a non-negative multiple of 16");
+  if (bytes == 0) return SWIFT_OK;
+  if (!dst_device || !src_device) return fail(SWIFT_EINVAL, "stream_copy: NULL pointer");
+  if (((uintptr_t)dst_device | (uintptr_t)src_device) & 15) return fail(SWIFT_EINVAL, "stream_copy: pointers must be 16-byte aligned");
+  int dev = -1, rc;
+  SWIFT_HIP(hipGetDevice(&dev));
+  DeviceInfo info;
+  if ((rc = device_info(dev, &info))) return rc;
+  if ((rc = check_device_range(dst_device, (size_t)bytes, dev, "dst_device", 0))) return rc;
+  if ((rc = check_device_range(src_device, (size_t)bytes, dev, "src_device", 0))) return rc;
+  const char *d = static_cast<const char *>(dst_device), *s = static_cast<const char *>(src_device);
+  if (d < s + bytes && s < d + bytes) return fail(SWIFT_EINVAL, "stream_copy: ranges overlap");
+  const auto kernel = copy_kernel<SWIFT_NT != 0, SWIFT_UNROLL>;
+  int per_cu = 1;
+  if ((rc = resident_groups(reinterpret_cast<const void *>(kernel), &per_cu))) return rc;
+  const uint64_t n16 = (uint64_t)bytes / 16;
+  const uint64_t tiles = (n16 + (uint64_t)SWIFT_UNROLL * kThreads - 1) / ((uint64_t)SWIFT_UNROLL * kThreads);
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, (uint64_t)info.cus * (uint64_t)per_cu);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<u32x4 *>(dst_device), static_cast<const u32x4 *>(src_device), n16);
+  SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+int swift_shutdown(void) {
+  std::list<std::shared_ptr<Plan>> drop;
+  {
+    std::lock_guard<std::mutex> lock(g_plan_mu);
+    if (g_plans) drop.swap(*g_plans);
+  }
+  drop.clear();   // ~Plan frees (and thereby synchronises) on each plan's device
+  return SWIFT_OK;
+}
+
+const char *swift_last_error(void) { return g_last_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,148 @@
+// State-digest kernels for gfx950.
+//
+// The digest of a shard is the modulo-2^64 sum of a bijectively mixed (index, word) pair per
+// 32-bit word, so partial sums can be combined in any order: lanes accumulate privately, a
+// wavefront combines its 64 lanes with DPP row operations and cross-row lane reads, the four
+// wavefronts of a workgroup meet in LDS, and one 64-bit atomic add per chunk lands in the output.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "opt_kernels.hpp"
+
+namespace swift {
+
+struct DigestDesc {        // one per buffer, 24 bytes, device resident
+  const uint32_t *w;       // raw 32-bit words
+  int64_t numel;
+  uint64_t first_out;      // index of this buffer's first shard in the output array
+};
+
+constexpr uint64_t kK1 = 0x9E3779B97F4A7C15ull;
+constexpr uint64_t kK2 = 0x6A09E667F3BCC909ull;
+constexpr uint64_t kK3 = 0xBB67AE8584CAA73Bull;
+
+// z = (i << 32) | w;  z += K1;  z ^= z >> 32;  z *= K2;  z ^= z >> 29;  z *= K3;  z ^= z >> 32
+__device__ __forceinline__ uint64_t digest_mix(uint32_t i, uint32_t w) {
+  uint64_t z = ((uint64_t)i << 32) | (uint64_t)w;
+  z += kK1;
+  z ^= z >> 32;
+  z *= kK2;
+  z ^= z >> 29;
+  z *= kK3;
+  z ^= z >> 32;
+  return z;
+}
+
+// Lane exchange inside a row of 16 lanes through the DPP data path.
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_fetch_u64(uint64_t s) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)s, CTRL, 0xF, 0xF, true);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(s >> 32), CTRL, 0xF, 0xF, true);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Sum of `s` over the 64 lanes of the wavefront (mod 2^64); the result is wave-uniform.
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t s) {
+  s += dpp_fetch_u64<0xB1>(s);    // quad_perm [1,0,3,2]: lane ^ 1
+  s += dpp_fetch_u64<0x4E>(s);    // quad_perm [2,3,0,1]: lane ^ 2   -> every lane holds its quad's sum
+  s += dpp_fetch_u64<0x141>(s);   // row_half_mirror: lane i <-> 7-i   -> sum of 8
+  s += dpp_fetch_u64<0x140>(s);   // row_mirror:      lane i <-> 15-i  -> sum of the row of 16
+  uint64_t total = 0;
+#pragma unroll
+  for (int row = 0; row < 4; ++row) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)s, row * 16);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(s >> 32), row * 16);
+    total += ((uint64_t)hi << 32) | lo;
+  }
+  return total;
+}
+
+__global__ void __launch_bounds__(kThreads) fill_u64_kernel(uint64_t *p, uint64_t n, uint64_t value) {
+  for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kThreads)
+    p[i] = value;
+}
+
+// Chunk numbering inside a buffer: a full shard spans cps = ceil(S / chunk_elems) chunk numbers,
+// chunk = shard * cps + k covers words [shard*S + k*CE, ...) of the buffer, i.e. shard-relative
+// indices [k*CE, min(k*CE + CE, shard length)).  S = shard_elems, or numel when shard_elems = 0.
+// `out` must be zero when the kernel starts.
+template <bool NT, int U>
+__global__ void __launch_bounds__(kThreads)
+digest_kernel(const DigestDesc *__restrict__ descs, const ChunkRef *__restrict__ chunks, uint32_t n_chunks,
+              uint32_t chunk_elems, uint64_t shard_elems, unsigned long long *__restrict__ out) {
+  __shared__ uint64_t wave_part[kThreads / 64];
+  const uint32_t tid = threadIdx.x;
+  for (uint32_t ci = blockIdx.x; ci < n_chunks; ci += gridDim.x) {
+    const ChunkRef ch = chunks[ci];
+    const DigestDesc d = descs[ch.tensor];
+    const uint64_t S = shard_elems ? shard_elems : (uint64_t)d.numel;
+    const uint32_t cps = (uint32_t)((S + chunk_elems - 1) / chunk_elems);
+    const uint32_t shard = ch.chunk / cps;
+    const uint32_t k = ch.chunk - shard * cps;
+    const uint64_t shard_off = (uint64_t)shard * S;
+    const uint64_t rest = (uint64_t)d.numel - shard_off;
+    const uint64_t shard_len = rest < S ? rest : S;
+    const uint32_t idx0 = k * chunk_elems;                       // shard-relative index of the chunk's first word
+    const uint64_t left = shard_len - idx0;
+    const uint32_t len = left < chunk_elems ? (uint32_t)left : chunk_elems;
+    const uint32_t *__restrict__ p = d.w + shard_off + idx0;
+
+    // head: words before the first 16-byte boundary; body: 16-byte vectors; tail: the rest
+    uint32_t head = (uint32_t)(((16u - (uint32_t)((uintptr_t)p & 15u)) & 15u) >> 2);
+    if (head > len) head = len;
+    const uint32_t n4 = (len - head) >> 2;
+    const uint32_t tail0 = head + (n4 << 2);
+    const u32x4 *__restrict__ p4 = reinterpret_cast<const u32x4 *>(p + head);
+    const uint32_t ib = idx0 + head;                             // shard-relative index of the body's first word
+
+    uint64_t acc = 0;
+    if (tid < head) acc += digest_mix(idx0 + tid, ld<false>(p + tid));
+    uint32_t i = 0;
+    for (; i + U * kThreads <= n4; i += U * kThreads) {
+      u32x4 r[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) r[u] = ld<NT>(p4 + i + u * kThreads + tid);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t e = ib + ((i + u * kThreads + tid) << 2);
+        acc += digest_mix(e, r[u][0]) + digest_mix(e + 1, r[u][1]);
+        acc += digest_mix(e + 2, r[u][2]) + digest_mix(e + 3, r[u][3]);
+      }
+    }
+    for (uint32_t j = i + tid; j < n4; j += kThreads) {
+      const u32x4 r = ld<NT>(p4 + j);
+      const uint32_t e = ib + (j << 2);
+      acc += digest_mix(e, r[0]) + digest_mix(e + 1, r[1]);
+      acc += digest_mix(e + 2, r[2]) + digest_mix(e + 3, r[3]);
+    }
+    if (tail0 + tid < len) acc += digest_mix(idx0 + tail0 + tid, ld<false>(p + tail0 + tid));
+
+    const uint64_t wsum = wave_sum_u64(acc);
+    if ((tid & 63u) == 0) wave_part[tid >> 6] = wsum;
+    __syncthreads();
+    if (tid == 0) {
+      uint64_t t = 0;
+#pragma unroll
+      for (int wv = 0; wv < kThreads / 64; ++wv) t += wave_part[wv];
+      atomicAdd(out + d.first_out + shard, (unsigned long long)t);
+    }
+    __syncthreads();                                             // wave_part is reused by the next chunk
+  }
+}
+
+// mask[i] = 1 if tensor i's digest differs in any of the n_groups group-major digest rows.
+__global__ void __launch_bounds__(kThreads)
+mask_from_digests_kernel(uint32_t n_tensors, uint32_t n_groups, const uint64_t *__restrict__ before,
+                         const uint64_t *__restrict__ after, uint8_t *__restrict__ mask) {
+  for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < n_tensors; i += gridDim.x * kThreads) {
+    uint8_t changed = 0;
+    for (uint32_t gI = 0; gI < n_groups; ++gI) {
+      const uint64_t j = (uint64_t)gI * n_tensors + i;
+      changed |= (before[j] != after[j]) ? 1 : 0;
+    }
+    mask[i] = changed;
+  }
+}
+
+}  // namespace swift

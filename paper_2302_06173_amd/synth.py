@@ -1,0 +1,178 @@
+"""Seeded synthetic workloads: tensor-shape lists and value distributions.
+
+This module holds NO optimizer or digest arithmetic.  It only says which shapes a workload has
+and how its inputs are drawn, so that the GPU library, the CPU oracle and the benchmark can all
+be fed the same bits.  The shape lists stand in for the models the paper trains (ResNet-50-class
+CNNs, BERT-large, GPT-class transformers); datasets and trained weights are not needed because
+the update path depends only on shapes and value distributions.
+
+Draw order (fixed, so a seed defines the bits): for each tensor in list order: theta, g, m, v;
+then, if requested, the zero mask and the outlier mask of g.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+Shape = Tuple[int, ...]
+
+
+def numel(shape: Shape) -> int:
+    n = 1
+    for s in shape:
+        n *= s
+    return n
+
+
+def resnet50_shapes() -> List[Shape]:
+    """Standard ResNet-50: 161 tensors, 25,557,032 parameters."""
+    out: List[Shape] = [(64, 3, 7, 7), (64,), (64,)]
+    cin = 64
+    for width, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for b in range(blocks):
+            out += [(width, cin, 1, 1), (width,), (width,),
+                    (width, width, 3, 3), (width,), (width,),
+                    (4 * width, width, 1, 1), (4 * width,), (4 * width,)]
+            if b == 0:
+                out += [(4 * width, cin, 1, 1), (4 * width,), (4 * width,)]
+            cin = 4 * width
+    out += [(1000, 2048), (1000,)]
+    return out
+
+
+def bert_large_shapes() -> List[Shape]:
+    """BERT-large encoder with pooler: 391 tensors, 335,141,888 parameters."""
+    h, f = 1024, 4096
+    out: List[Shape] = [(30522, h), (512, h), (2, h), (h,), (h,)]
+    for _ in range(24):
+        for _ in range(4):
+            out += [(h, h), (h,)]
+        out += [(h,), (h,), (f, h), (f,), (h, f), (h,), (h,), (h,)]
+    out += [(h, h), (h,)]
+    return out
+
+
+def gpt2_xl_shapes() -> List[Shape]:
+    """GPT-2 1.5B: 580 tensors, 1,557,611,200 parameters."""
+    d, f = 1600, 6400
+    out: List[Shape] = [(50257, d), (1024, d)]
+    for _ in range(48):
+        out += [(d,), (d,), (d, 3 * d), (3 * d,), (d, d), (d,), (d,), (d,), (d, f), (f,), (f, d), (d,)]
+    out += [(d,), (d,)]
+    return out
+
+
+def llama7b_shapes() -> List[Shape]:
+    """Llama-7B: 291 tensors, 6,738,415,616 parameters."""
+    d, f, vocab = 4096, 11008, 32000
+    out: List[Shape] = [(vocab, d)]
+    for _ in range(32):
+        out += [(d, d)] * 4 + [(f, d)] * 2 + [(d, f)] + [(d,)] * 2
+    out += [(d,), (vocab, d)]
+    return out
+
+
+@dataclass
+class Workload:
+    """One benchmark / parity configuration: shapes, value recipe and hyper-parameters."""
+    name: str
+    shapes: List[Shape]
+    kind: str                      # "sgdm" | "adam" | "adamw"
+    hyper: dict                    # lr, weight_decay, momentum, dampening, beta1, beta2, eps, step
+    seed: int
+    grad_bf16: bool = False
+    std_theta: float = 0.02
+    std_grad: float = 1e-3
+    std_m: float = 1e-4
+    std_v: float = 1e-6
+    zero_frac: float = 0.0         # fraction of gradient elements forced to zero
+    outlier_frac: float = 0.0      # fraction of gradient elements multiplied by outlier_scale
+    outlier_scale: float = 1e3
+    digest_shard: int = 0          # 0: one digest per tensor; else fixed shard length
+    masked_fraction: float = 0.0   # selective step/undo on this fraction of the tensors
+    extra: dict = field(default_factory=dict)
+
+    @property
+    def n_params(self) -> int:
+        return sum(numel(s) for s in self.shapes)
+
+
+_ADAM = dict(lr=1e-3, weight_decay=0.0, beta1=0.9, beta2=0.999, eps=1e-8)
+
+
+def workloads() -> dict:
+    """The five configurations, smallest first."""
+    return {
+        "sgdm_flat_1m": Workload(
+            "sgdm_flat_1m", [(1 << 20,)], "sgdm",
+            dict(lr=0.1, momentum=0.9, dampening=0.0, weight_decay=1e-4, step=1),
+            seed=1, std_m=1e-3, digest_shard=1 << 16),
+        "resnet50_adam": Workload(
+            "resnet50_adam", resnet50_shapes(), "adam", dict(_ADAM, step=1000), seed=2),
+        "bert_large_adamw": Workload(
+            "bert_large_adamw", bert_large_shapes(), "adamw", dict(_ADAM, weight_decay=0.01, step=10000), seed=3),
+        "gpt2_xl_adamw_bf16g": Workload(
+            "gpt2_xl_adamw_bf16g", gpt2_xl_shapes(), "adamw",
+            dict(lr=6e-4, weight_decay=0.1, beta1=0.9, beta2=0.95, eps=1e-8, step=50000), seed=4, grad_bf16=True),
+        # the configuration gives no lr/betas/eps/decay of its own: the GPT-2 values are used
+        "llama7b_adamw": Workload(
+            "llama7b_adamw", llama7b_shapes(), "adamw",
+            dict(lr=6e-4, weight_decay=0.1, beta1=0.9, beta2=0.95, eps=1e-8, step=100000), seed=5,
+            zero_frac=0.10, outlier_frac=0.01, masked_fraction=0.5),
+    }
+
+
+@dataclass
+class State:
+    """Tensor lists of one replica: theta, gradient, first moment, second moment (None for SGDM)."""
+    theta: List[torch.Tensor]
+    grad: List[torch.Tensor]
+    m: List[torch.Tensor]
+    v: Optional[List[torch.Tensor]]
+
+    def clone(self) -> "State":
+        c = lambda ts: None if ts is None else [t.clone() for t in ts]
+        return State(c(self.theta), c(self.grad), c(self.m), c(self.v))
+
+
+def make_state(w: Workload, device, shapes: Optional[Sequence[Shape]] = None, with_v: Optional[bool] = None) -> State:
+    """Draw the workload's state on `device` (same seed and device type => same bits)."""
+    shapes = list(w.shapes if shapes is None else shapes)
+    with_v = (w.kind != "sgdm") if with_v is None else with_v
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    th, gr, mo, vo = [], [], [], []
+    for shp in shapes:
+        n = numel(shp)
+        x = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_theta, generator=gen)
+        g = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_grad, generator=gen)
+        m = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_m, generator=gen)
+        if with_v:
+            v = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_v, generator=gen).abs_()
+            vo.append(v)
+        if w.zero_frac > 0 or w.outlier_frac > 0:
+            r = torch.empty(n, dtype=torch.float32, device=dev).uniform_(0.0, 1.0, generator=gen)
+            g[r < w.zero_frac] = 0.0
+            g[r >= 1.0 - w.outlier_frac] *= w.outlier_scale
+            del r
+        if w.grad_bf16:
+            g = g.to(torch.bfloat16)      # round to nearest even; the kernels widen it back exactly
+        th.append(x)
+        gr.append(g)
+        mo.append(m)
+    return State(th, gr, mo, vo if with_v else None)
+
+
+def tensor_mask(w: Workload, n_tensors: int) -> List[int]:
+    """Seeded choice of which tensors a partial step reaches (the paper's 'marked as updated' set)."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(w.seed + 1000)
+    k = int(round(w.masked_fraction * n_tensors))
+    perm = torch.randperm(n_tensors, generator=gen)[:k]
+    mask = [0] * n_tensors
+    for i in perm.tolist():
+        mask[i] = 1
+    return mask

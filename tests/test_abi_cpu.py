@@ -1,0 +1,151 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header declares, and rejects
+bad arguments before touching any GPU.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2302_06173_amd import build
+    build.build(force=False)
+    from paper_2302_06173_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(B):
+    text = open(os.path.join(ROOT, "include", "swift_undo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(swift_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B._lib, name), name
+
+
+def test_struct_layouts_match_the_header(B):
+    # int32, int32, int64, 7 doubles / int64 + 5 pointers: no padding surprises
+    assert ctypes.sizeof(B.SwiftHparams) == 4 + 4 + 8 + 7 * 8
+    assert ctypes.sizeof(B.SwiftTensorList) == 8 + 5 * 8
+    assert B.SwiftHparams.lr.offset == 16 and B.SwiftHparams.eps.offset == 64
+
+
+def test_digest_count_is_host_arithmetic(B):
+    assert B.swift_digest_count([], 0) == 0
+    assert B.swift_digest_count([10, 0, 3], 0) == 3
+    assert B.swift_digest_count([10, 0, 3], 4) == 3 + 0 + 1
+    assert B.swift_digest_count([1 << 20], 1 << 16) == 16
+    assert B.swift_digest_count([(1 << 32) + 5], 1 << 31) == 3
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_digest_count([1 << 32], 0)           # one shard of 2^32 words: index would not fit
+    assert e.value.code == B.SWIFT_EINVAL and "shard_elems" in e.value.message
+    with pytest.raises(B.SwiftError):
+        B.swift_digest_count([-1], 0)
+    with pytest.raises(B.SwiftError):
+        B.swift_digest_count([4], 1 << 32)
+    with pytest.raises(B.SwiftError):
+        B.swift_digest_count([4], -1)
+
+
+def _call(B, fn, hp, n=0):
+    lst = B.SwiftTensorList(n, None, None, None, None, None)
+    return getattr(B._lib, fn)(ctypes.byref(lst), ctypes.byref(hp), None, None)
+
+
+@pytest.mark.parametrize("fn", ["swift_opt_step", "swift_opt_undo"])
+def test_hyper_parameter_domain(B, fn):
+    ok = B.hparams("adamw", step=5, lr=1e-3, weight_decay=0.01)
+    assert _call(B, fn, ok) == B.SWIFT_OK                       # empty list: nothing to do
+    bad = [
+        B.hparams(7, step=1, lr=0.1),
+        B.hparams("adam", step=0, lr=0.1),
+        B.hparams("adam", step=1, lr=float("nan")),
+        B.hparams("adam", step=1, lr=float("inf")),
+        B.hparams("adam", step=1, lr=0.1, weight_decay=-1.0),
+        B.hparams("adam", step=1, lr=0.1, beta1=1.0),
+        B.hparams("adam", step=1, lr=0.1, beta2=-0.1),
+        B.hparams("adamw", step=1, lr=0.1, eps=-1e-8),
+        B.hparams("sgdm", step=1, lr=0.1, momentum=1.5),
+        B.hparams("sgdm", step=1, lr=0.1, dampening=-0.5),
+    ]
+    for hp in bad:
+        assert _call(B, fn, hp) == B.SWIFT_EINVAL
+        assert B.swift_last_error() != ""
+    hp = B.hparams("adam", step=1, lr=0.1)
+    hp.grad_dtype = 9
+    assert _call(B, fn, hp) == B.SWIFT_EINVAL
+
+
+def test_not_invertible_is_an_undo_only_error(B):
+    for hp in (B.hparams("adam", step=1, lr=0.1, beta1=0.0),
+               B.hparams("adamw", step=1, lr=0.1, beta2=0.0),
+               B.hparams("adamw", step=1, lr=0.5, weight_decay=2.0)):
+        assert _call(B, "swift_opt_undo", hp) == B.SWIFT_ENOTINVERTIBLE
+        assert "divides" in B.swift_last_error()
+        assert _call(B, "swift_opt_step", hp) == B.SWIFT_OK
+    # momentum 0 is the paper's plain SGD: undo is allowed
+    assert _call(B, "swift_opt_undo", B.hparams("sgdm", step=1, lr=0.1, momentum=0.0)) == B.SWIFT_OK
+
+
+def test_null_and_negative_arguments(B):
+    hp = B.hparams("adam", step=1, lr=0.1)
+    assert B._lib.swift_opt_step(None, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    lst = B.SwiftTensorList(2, None, None, None, None, None)
+    assert B._lib.swift_opt_step(ctypes.byref(lst), None, None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "NULL" in B.swift_last_error()
+    lst = B.SwiftTensorList(-1, None, None, None, None, None)
+    assert B._lib.swift_opt_undo(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    # numel < 0, missing v for Adam, misaligned pointer: all caught on the host
+    n = 1
+    ptr = (ctypes.c_void_p * 1)(0x1000)
+    odd = (ctypes.c_void_p * 1)(0x1002)
+    P = ctypes.POINTER(ctypes.c_void_p)
+    neg = (ctypes.c_int64 * 1)(-5)
+    four = (ctypes.c_int64 * 1)(4)
+    c = lambda a: ctypes.cast(a, P)
+    i64 = lambda a: ctypes.cast(a, ctypes.POINTER(ctypes.c_int64))
+    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), c(ptr), i64(neg))
+    assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), None, i64(four))
+    assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "v array" in B.swift_last_error()
+    lst = B.SwiftTensorList(n, c(odd), c(ptr), c(ptr), c(ptr), i64(four))
+    assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "aligned" in B.swift_last_error()
+    # bf16 gradients may sit on 2-byte boundaries, fp32 gradients may not
+    lst = B.SwiftTensorList(n, c(ptr), c(odd), c(ptr), c(ptr), i64(four))
+    assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_mask_from_digests(-1, 3, None, None, None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_mask_from_digests(4, 0, None, None, None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_mask_from_digests(4, 3, None, None, None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_mask_from_digests(0, 3, None, None, None, None) == B.SWIFT_OK
+    assert B._lib.swift_stream_copy(None, None, 8, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_stream_copy(None, None, 16, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_stream_copy(None, None, 0, None) == B.SWIFT_OK
+    assert B._lib.swift_state_digest(-1, None, None, 0, None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_state_digest(0, None, None, 0, None, None) == B.SWIFT_OK
+    assert B._lib.swift_shutdown() == B.SWIFT_OK
+
+
+def test_synthetic_workloads_have_the_stated_sizes():
+    from paper_2302_06173_amd import synth
+    w = synth.workloads()
+    got = {k: (len(v.shapes), v.n_params) for k, v in w.items()}
+    assert got == {
+        "sgdm_flat_1m": (1, 1_048_576),
+        "resnet50_adam": (161, 25_557_032),
+        "bert_large_adamw": (391, 335_141_888),
+        "gpt2_xl_adamw_bf16g": (580, 1_557_611_200),
+        "llama7b_adamw": (291, 6_738_415_616),
+    }
+    # seeded: same seed, same bits; the mask picks the stated fraction
+    s1 = synth.make_state(w["sgdm_flat_1m"], "cpu", shapes=[(33,), (5,)])
+    s2 = synth.make_state(w["sgdm_flat_1m"], "cpu", shapes=[(33,), (5,)])
+    assert all((a == b).all() for a, b in zip(s1.theta + s1.grad + s1.m, s2.theta + s2.grad + s2.m))
+    assert s1.v is None
+    mask = synth.tensor_mask(w["llama7b_adamw"], 291)
+    assert sum(mask) == 146 and mask == synth.tensor_mask(w["llama7b_adamw"], 291)

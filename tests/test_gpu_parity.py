@@ -1,0 +1,395 @@
+"""GPU parity: the HIP library, called through its C ABI binding, against the fp64 CPU oracle on the
+same seeded input bits, element by element.  Floating point: |gpu - oracle| <= max(1e-5 |oracle|,
+1e-8) per element (plus the stricter one-ulp check of gpu_util.assert_parity); digests, masks and
+everything that must not change: bit-exact."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_parity, binding_hparams, digests_np, oracle_hyper, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2302_06173_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2302_06173_amd import synth
+    return synth
+
+
+HP = {
+    "sgdm": dict(lr=0.1, momentum=0.9, dampening=0.1, weight_decay=1e-4, step=1),
+    "adam": dict(lr=1e-3, weight_decay=0.01, beta1=0.9, beta2=0.999, eps=1e-8, step=1000),
+    "adamw": dict(lr=6e-4, weight_decay=0.1, beta1=0.9, beta2=0.95, eps=1e-8, step=7),
+}
+# several chunks (4096 elements each at this size), ragged tails of every residue mod 4, a
+# one-element and an empty tensor
+SHAPES = [(5000,), (1,), (0,), (4096,), (33333,), (2051,), (70001,), (8192 + 2,), (7,)]
+
+
+def snapshot(state):
+    f = lambda ts: None if ts is None else [to_np(t) for t in ts]
+    return f(state.theta), f(state.grad), f(state.m), f(state.v)
+
+
+def in_scale(*arrs):
+    s = 0.0
+    for a in arrs:
+        if a is None or a.size == 0:
+            continue
+        a = oracle.widen(a)
+        a = a[np.isfinite(a)]
+        if a.size:
+            s = max(s, float(np.abs(a).max()))
+    return s
+
+
+def check_against_oracle(kind, hp, pre, post, mask, undo, what):
+    """pre/post: host snapshots (theta, grad, m, v) around ONE GPU call; mask: per tensor or None."""
+    h = oracle_hyper(kind, hp)
+    fn = oracle.opt_undo if undo else oracle.opt_step
+    px, pg, pm, pv = pre
+    qx, qg, qm, qv = post
+    worst = 0.0
+    for i in range(len(px)):
+        assert np.array_equal(pg[i].view(np.uint8), qg[i].view(np.uint8)), f"{what}: gradient {i} was written"
+        if mask is not None and not mask[i]:
+            assert np.array_equal(px[i].view(np.uint32), qx[i].view(np.uint32)), f"{what}: masked theta {i} changed"
+            assert np.array_equal(pm[i].view(np.uint32), qm[i].view(np.uint32)), f"{what}: masked m {i} changed"
+            if pv is not None:
+                assert np.array_equal(pv[i].view(np.uint32), qv[i].view(np.uint32)), f"{what}: masked v {i} changed"
+            continue
+        v_in = None if pv is None else pv[i]
+        rx, rm, rv = fn(h, px[i], pg[i], pm[i], v_in)
+        scale = in_scale(px[i], pg[i], pm[i], v_in)
+        worst = max(worst, assert_parity(qx[i], rx, f"{what} theta[{i}]", scale))
+        assert_parity(qm[i], rm, f"{what} m[{i}]", scale)
+        if pv is not None:
+            assert_parity(qv[i], rv, f"{what} v[{i}]", scale * max(scale, 1.0))
+    return worst
+
+
+def make(synth, kind, shapes, seed=11, bf16=False, zero_frac=0.1, outlier_frac=0.01):
+    w = synth.Workload("t", list(shapes), kind, HP[kind], seed=seed, grad_bf16=bf16, zero_frac=zero_frac,
+                       outlier_frac=outlier_frac, std_m=1e-3 if kind == "sgdm" else 1e-4)
+    return synth.make_state(w, "cuda")
+
+
+def tensor_list(B, s):
+    return B.TensorList(s.theta, s.grad, s.m, s.v)
+
+
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True], ids=["g_f32", "g_bf16"])
+@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+def test_step_then_undo_match_oracle_elementwise(B, synth, kind, bf16):
+    s = make(synth, kind, SHAPES, bf16=bf16)
+    tl = tensor_list(B, s)
+    hp = binding_hparams(B, kind, HP[kind], bf16)
+    orig = snapshot(s)
+    B.swift_opt_step(tl, hp)
+    torch.cuda.synchronize()
+    stepped = snapshot(s)
+    check_against_oracle(kind, HP[kind], orig, stepped, None, False, f"{kind} step")
+    # parity of the undo: oracle and GPU both start from the GPU's post-step bits
+    B.swift_opt_undo(tl, hp)
+    torch.cuda.synchronize()
+    undone = snapshot(s)
+    check_against_oracle(kind, HP[kind], stepped, undone, None, True, f"{kind} undo")
+    # round trip against the originals: bounded by what the step's rounding destroyed; on the
+    # non-outlier population (|g| < 0.01) it stays inside the 1e-5 / 1e-8 bar
+    for i in range(len(orig[0])):
+        g = oracle.widen(orig[1][i])
+        calm = np.abs(g) < 1e-2
+        for k in (0, 2, 3):
+            if orig[k] is None:
+                continue
+            a, b = undone[k][i].astype(np.float64)[calm], orig[k][i].astype(np.float64)[calm]
+            assert (np.abs(a - b) <= np.maximum(1e-5 * np.abs(b), 1e-8)).all(), (kind, i, k)
+
+
+@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+def test_alignment_does_not_change_result_bits(B, synth, kind):
+    # the same values at 16-byte-aligned addresses and at addresses 4 (or 2, bf16) bytes past one
+    shapes = [(4099,), (130,), (9000,)]
+    for bf16 in (False, True):
+        a = make(synth, kind, shapes, seed=5, bf16=bf16)
+        def shifted(ts):
+            out = []
+            for t in ts:
+                buf = torch.empty(t.numel() + 8, dtype=t.dtype, device="cuda")
+                view = buf[1:1 + t.numel()]
+                view.copy_(t)
+                assert view.data_ptr() % 16 != 0
+                out.append(view)
+            return out
+        b = synth.State(shifted(a.theta), shifted(a.grad), shifted(a.m), None if a.v is None else shifted(a.v))
+        hp = binding_hparams(B, kind, HP[kind], bf16)
+        for fn in (B.swift_opt_step, B.swift_opt_undo):
+            fn(tensor_list(B, a), hp)
+            fn(tensor_list(B, b), hp)
+            torch.cuda.synchronize()
+            for x, y in zip(snapshot(a), snapshot(b)):
+                if x is None:
+                    continue
+                for p, q in zip(x, y):
+                    assert np.array_equal(p.view(np.uint8), q.view(np.uint8))
+    # and the unaligned path itself matches the oracle
+    s = b
+    pre = snapshot(s)
+    B.swift_opt_step(tensor_list(B, s), hp)
+    torch.cuda.synchronize()
+    check_against_oracle(kind, HP[kind], pre, snapshot(s), None, False, f"{kind} unaligned step")
+
+
+@pytest.mark.parametrize("kind", ["sgdm", "adamw"])
+def test_host_mask_and_device_mask(B, synth, kind):
+    shapes = [(3000,), (5,), (4096,), (10000,), (0,), (777,)]
+    mask = [1, 0, 1, 0, 1, 1]
+    s1 = make(synth, kind, shapes, seed=21)
+    s2 = s1.clone()
+    hp = binding_hparams(B, kind, HP[kind])
+    pre = snapshot(s1)
+    B.swift_opt_step(tensor_list(B, s1), hp, host_mask=mask)
+    dm = torch.tensor(mask, dtype=torch.uint8, device="cuda")
+    B.swift_opt_step_dmask(tensor_list(B, s2), hp, dm)
+    torch.cuda.synchronize()
+    post1, post2 = snapshot(s1), snapshot(s2)
+    check_against_oracle(kind, HP[kind], pre, post1, mask, False, f"{kind} masked step")
+    for x, y in zip(post1, post2):
+        if x is not None:
+            assert all(np.array_equal(p.view(np.uint32), q.view(np.uint32)) for p, q in zip(x, y))
+    # undo exactly the tensors marked as updated
+    B.swift_opt_undo(tensor_list(B, s1), hp, host_mask=mask)
+    B.swift_opt_undo_dmask(tensor_list(B, s2), hp, dm)
+    torch.cuda.synchronize()
+    und1, und2 = snapshot(s1), snapshot(s2)
+    check_against_oracle(kind, HP[kind], post1, und1, mask, True, f"{kind} masked undo")
+    for x, y in zip(und1, und2):
+        if x is not None:
+            assert all(np.array_equal(p.view(np.uint32), q.view(np.uint32)) for p, q in zip(x, y))
+    # an all-zero mask does nothing; an all-one mask equals no mask
+    before = snapshot(s1)
+    B.swift_opt_step(tensor_list(B, s1), hp, host_mask=[0] * len(shapes))
+    torch.cuda.synchronize()
+    for x, y in zip(before, snapshot(s1)):
+        if x is not None:
+            assert all(np.array_equal(p.view(np.uint32), q.view(np.uint32)) for p, q in zip(x, y))
+
+
+def test_special_values_and_degenerate_hyper_parameters(B, synth):
+    # NaN / Inf propagate as in IEEE arithmetic, denormals survive, -0.0 is kept, mu = 0 works
+    n = 4096 + 64
+    for kind in ("sgdm", "adam", "adamw"):
+        s = make(synth, kind, [(n,)], seed=31, zero_frac=0.2)
+        g = s.grad[0]
+        g[0], g[1], g[2] = float("nan"), float("inf"), float("-inf")
+        s.theta[0][3] = float("nan")
+        s.m[0][4] = 1e-41                      # binary32 denormal
+        s.m[0][5] = -0.0
+        g[5] = 0.0
+        g[6] = 1e-42
+        s.theta[0][7] = 3e-39
+        if s.v is not None:
+            s.v[0][8] = 1e-44
+            s.v[0][9] = 0.0
+            g[9] = 0.0
+            s.m[0][9] = 0.0
+        hps = [HP[kind]]
+        if kind == "sgdm":
+            hps.append(dict(HP[kind], momentum=0.0))
+            hps.append(dict(HP[kind], lr=0.0))
+        else:
+            hps.append(dict(HP[kind], eps=0.0, weight_decay=0.0, step=1))
+        for hpd in hps:
+            hp = binding_hparams(B, kind, hpd)
+            tl = tensor_list(B, s)
+            pre = snapshot(s)
+            B.swift_opt_step(tl, hp)
+            torch.cuda.synchronize()
+            mid = snapshot(s)
+            check_against_oracle(kind, hpd, pre, mid, None, False, f"{kind} special step")
+            B.swift_opt_undo(tl, hp)
+            torch.cuda.synchronize()
+            check_against_oracle(kind, hpd, mid, snapshot(s), None, True, f"{kind} special undo")
+            s.theta[0].nan_to_num_(0.01, 0.01, -0.01)     # keep the next round finite where it was
+            s.m[0].nan_to_num_(1e-4, 1e-4, -1e-4)
+            if s.v is not None:
+                s.v[0].nan_to_num_(1e-6, 1e-6, 1e-6).abs_()
+
+
+def test_denormal_state_is_neither_flushed_nor_rounded_away(B, synth):
+    # every input is tiny, so the one-ulp check has no slack: results must equal the oracle's value
+    # rounded to binary32, in the denormal range too
+    n = 5000
+    tiny = torch.tensor([1e-41, -3e-42, 1.4e-45, 2e-39, -1.1e-38, 5e-38, 0.0, -0.0], device="cuda")
+    reps = (n + tiny.numel() - 1) // tiny.numel()
+    for kind in ("sgdm", "adam", "adamw"):
+        hpd = dict(HP[kind], weight_decay=0.0 if kind != "adamw" else 0.1)
+        x = tiny.repeat(reps)[:n].clone()
+        m = tiny.flip(0).repeat(reps)[:n].clone()
+        g = torch.zeros(n, device="cuda")
+        g[1::5] = 1e-40
+        v = tiny.abs().roll(3).repeat(reps)[:n].clone() if kind != "sgdm" else None
+        s = synth.State([x], [g], [m], None if v is None else [v])
+        hp = binding_hparams(B, kind, hpd)
+        pre = snapshot(s)
+        B.swift_opt_step(tensor_list(B, s), hp)
+        torch.cuda.synchronize()
+        mid = snapshot(s)
+        check_against_oracle(kind, hpd, pre, mid, None, False, f"{kind} denormal step")
+        assert (np.abs(mid[2][0][mid[2][0] != 0]) < 1.2e-38).any(), "no denormal result was produced"
+        B.swift_opt_undo(tensor_list(B, s), hp)
+        torch.cuda.synchronize()
+        check_against_oracle(kind, hpd, mid, snapshot(s), None, True, f"{kind} denormal undo")
+
+
+def test_deterministic_and_on_a_side_stream(B, synth):
+    a = make(synth, "adamw", SHAPES, seed=41)
+    b = a.clone()
+    hp = binding_hparams(B, "adamw", HP["adamw"])
+    side = torch.cuda.Stream()
+    B.swift_opt_step(tensor_list(B, a), hp)
+    side.wait_stream(torch.cuda.current_stream())
+    B.swift_opt_step(tensor_list(B, b), hp, stream=side)
+    B.swift_opt_undo(tensor_list(B, b), hp, stream=side)      # stream order: step finishes first
+    B.swift_opt_undo(tensor_list(B, a), hp)
+    torch.cuda.synchronize()
+    for x, y in zip(snapshot(a), snapshot(b)):
+        assert all(np.array_equal(p.view(np.uint32), q.view(np.uint32)) for p, q in zip(x, y))
+
+
+def test_many_distinct_lists_survive_plan_eviction(B, synth):
+    # more distinct tensor lists than the library caches: tables are rebuilt, results stay right
+    hp = binding_hparams(B, "sgdm", HP["sgdm"])
+    states = [make(synth, "sgdm", [(1000 + 13 * k,), (k + 1,)], seed=100 + k) for k in range(40)]
+    pres = [snapshot(s) for s in states]
+    for rep in range(2):
+        for s in states:
+            (B.swift_opt_step if rep == 0 else B.swift_opt_undo)(tensor_list(B, s), hp)
+        torch.cuda.synchronize()
+        posts = [snapshot(s) for s in states]
+        for k, (pre, post) in enumerate(zip(pres, posts)):
+            check_against_oracle("sgdm", HP["sgdm"], pre, post, None, rep == 1, f"list {k}")
+        pres = posts
+
+
+# ------------------------------------------------------------------------------------------ errors
+def test_bad_device_arguments_are_rejected_on_the_host(B, synth):
+    s = make(synth, "adam", [(1000,), (64,)], seed=51)
+    hp = binding_hparams(B, "adam", HP["adam"])
+    before = snapshot(s)
+    # a host pointer where a device pointer belongs
+    host = torch.zeros(1000)
+    tl = tensor_list(B, s)
+    tl._param[0] = host.data_ptr()
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_opt_step(tl, hp)
+    assert e.value.code == B.SWIFT_EINVAL
+    # numel far beyond the allocation
+    tl = tensor_list(B, s)
+    tl._numel[1] = 1 << 34
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_opt_step(tl, hp)
+    assert e.value.code == B.SWIFT_EINVAL and "allocation" in e.value.message
+    # theta aliasing m
+    tl = tensor_list(B, s)
+    tl._m[0] = tl._param[0]
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_opt_undo(tl, hp)
+    assert e.value.code == B.SWIFT_EINVAL and "overlap" in e.value.message
+    # not invertible: nothing is enqueued, state untouched
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_opt_undo(tensor_list(B, s), binding_hparams(B, "adam", dict(HP["adam"], beta1=0.0)))
+    assert e.value.code == B.SWIFT_ENOTINVERTIBLE
+    with pytest.raises(ValueError):
+        B.swift_opt_step(tensor_list(B, s), hp, host_mask=[1])
+    # digest of a host buffer
+    ptrs = (ctypes.c_void_p * 1)(host.data_ptr())
+    rc = B._lib.swift_state_digest(1, ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p)), (ctypes.c_int64 * 1)(1000),
+                                   0, s.v[0].data_ptr(), None)
+    assert rc == B.SWIFT_EINVAL and B.swift_last_error() != ""
+    torch.cuda.synchronize()
+    for x, y in zip(before, snapshot(s)):
+        assert all(np.array_equal(p.view(np.uint32), q.view(np.uint32)) for p, q in zip(x, y))
+    # the library still works after the errors
+    B.swift_opt_step(tensor_list(B, s), hp)
+    torch.cuda.synchronize()
+    check_against_oracle("adam", HP["adam"], before, snapshot(s), None, False, "after errors")
+
+
+# ------------------------------------------------------------------------------------------ digest
+@pytest.mark.parametrize("shard", [0, 7, 256, 1000, 4096, 65536, 100000])
+def test_digest_bit_exact(B, shard):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(61)
+    sizes = [70001, 0, 1, 3, 4096, 16384 + 5, 200000, 65536]
+    bufs = [torch.empty(n, dtype=torch.float32, device="cuda").normal_(0, 1, generator=gen) for n in sizes]
+    bufs[4] = torch.randint(-2 ** 31, 2 ** 31 - 1, (4096,), dtype=torch.int32, device="cuda", generator=gen)
+    bufs[6][::3] = 0.0
+    bufs[6][1::7] = -0.0
+    # buffers that start 4, 8 and 12 bytes past a 16-byte boundary
+    for off in (1, 2, 3):
+        base = torch.empty(30000 + 8, dtype=torch.float32, device="cuda").normal_(0, 1, generator=gen)
+        bufs.append(base[off:off + 30000 - off])
+    out = B.swift_state_digest(bufs, shard)
+    torch.cuda.synchronize()
+    want = oracle.digest_list([to_np(b) for b in bufs], shard)
+    got = digests_np(out)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want), np.nonzero(got != want)[0][:8]
+    assert out.numel() == B.swift_digest_count([b.numel() for b in bufs], shard)
+    # a second call into the same (dirty) output overwrites it
+    out.fill_(-1)
+    B.swift_state_digest(bufs, shard, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(digests_np(out), want)
+
+
+def test_digest_detects_a_single_flipped_bit_and_drives_selective_undo(B, synth):
+    # the flow of a failure in mid-update: digests at iteration t, a step that reaches only some
+    # tensors, digests again, mask from the digests (on the device), undo exactly those tensors
+    kind = "adamw"
+    shapes = [(5000,), (64,), (4096,), (12345,), (0,), (300,), (20000,), (8,)]
+    stepped = [1, 0, 0, 1, 1, 1, 0, 1]
+    s = make(synth, kind, shapes, seed=71)
+    n = len(shapes)
+    hp = binding_hparams(B, kind, HP[kind])
+    tl = tensor_list(B, s)
+    state_bufs = B.BufferList(s.theta + s.m + s.v)
+    d0 = B.swift_state_digest(state_bufs, 0)
+    orig = snapshot(s)
+    B.swift_opt_step(tl, hp, host_mask=stepped)
+    d1 = B.swift_state_digest(state_bufs, 0)
+    dmask = B.swift_mask_from_digests(d0, d1, n)
+    B.swift_opt_undo_dmask(tl, hp, dmask)                 # no host round trip between these calls
+    torch.cuda.synchronize()
+    a, b = digests_np(d0).reshape(3, n), digests_np(d1).reshape(3, n)
+    want_mask = (a != b).any(axis=0).astype(np.uint8)
+    assert np.array_equal(dmask.cpu().numpy(), want_mask)
+    expect = np.array(stepped, np.uint8)
+    expect[4] = 0                                        # an empty tensor has nothing to change
+    assert np.array_equal(want_mask, expect)
+    assert np.array_equal(a, oracle.digest_list(orig[0] + orig[2] + orig[3], 0).reshape(3, n))
+    # after the selective undo every tensor is back within tolerance, untouched ones bit for bit
+    und = snapshot(s)
+    for i in range(n):
+        for k in (0, 2, 3):
+            if not expect[i]:
+                assert np.array_equal(und[k][i].view(np.uint32), orig[k][i].view(np.uint32))
+    # one flipped mantissa bit in one element of one buffer changes exactly that digest
+    d2 = B.swift_state_digest(state_bufs, 0)
+    s.m[6].view(torch.int32)[19999] ^= 1
+    d3 = B.swift_state_digest(state_bufs, 0)
+    torch.cuda.synchronize()
+    diff = np.nonzero(digests_np(d2) != digests_np(d3))[0]
+    assert diff.tolist() == [n + 6]
