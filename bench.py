@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the update-undo hot path on one MI355X.
+
+One "step" of this benchmark is one pass of the whole hot path over the workload's state, which is
+resident in HBM before the clock starts:
+
+  1. digest of theta, m, v per tensor                       (state at iteration t)
+  2. AdamW step on a seeded random half of the tensors      (an update interrupted by a failure)
+  3. digest again, 4. per-tensor "updated" mask from the two digest arrays (on the device)
+  5. AdamW undo of exactly the marked tensors               (selective undo)
+  6. full AdamW step + full AdamW undo
+  7. full Adam (coupled decay) step + undo
+  8. full SGD-momentum step + undo (theta, g, m only)
+
+`value` is the number of parameter updates and parameter undos carried out per second of wall
+time over that whole pass (digests and mask derivation are in the time, not in the count).  The
+`roofline` object describes the dominant kernel, AdamW undo (launched twice per pass: selective and
+full list): mean algorithmic bytes per launch (28 per parameter with fp32 gradients: theta, g, m, v
+in; theta, m, v out) over the mean launch duration, measured with HIP events on the launching
+stream inside the timed region.
+`cpu_baseline` times the fp64 CPU oracle on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "params/sec and HBM GB/s (% of roofline) for Adam update-undo, 1 MI355X"
+HBM_PEAK_GBS = 8000.0                 # MI355X published HBM3E bandwidth
+TRAFFIC_NOTE = os.path.join(ROOT, "profiles", "adamw_undo_llama7b_hbm_traffic.txt")
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per AdamW-undo launch from the committed rocprofv3 counter summary, if it covers
+    this workload (the counters cannot be read from inside this process)."""
+    try:
+        with open(TRAFFIC_NOTE) as fh:
+            rec = dict(l.split(":", 1) for l in fh if ":" in l and not l.startswith("#"))
+        if rec.get("workload", "").strip() == workload:
+            return float(rec["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
+def cpu_baseline(w, state, hp_dict, sample_elems: int):
+    """The oracle, as it stands, on the first `sample_elems` elements of the first tensor: AdamW
+    step then undo (its own fp64 state) plus the digest of theta, m and v; all cores, static split."""
+    import concurrent.futures as cf
+    import numpy as np
+    import oracle
+
+    n = min(sample_elems, state.theta[0].numel())
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    import torch
+
+    def host(t):
+        t = t[:n]
+        return (t if t.dtype == torch.float32 else t.float()).cpu().numpy()    # bf16 -> fp32 is exact
+
+    x32, g32, m32, v32 = host(state.theta[0]), host(state.grad[0]), host(state.m[0]), host(state.v[0])
+    x, g, m, v = (oracle.widen(a) for a in (x32, g32, m32, v32))
+    oh = oracle.Hyper("adamw", eta=hp_dict["lr"], lam=hp_dict["weight_decay"], beta1=hp_dict["beta1"],
+                      beta2=hp_dict["beta2"], eps=hp_dict["eps"], t=hp_dict["step"])
+    bounds = [n * k // cores for k in range(cores + 1)]
+
+    def work(k):
+        lo, hi = bounds[k], bounds[k + 1]
+        sx, sm, sv = oracle.opt_step(oh, x[lo:hi], g[lo:hi], m[lo:hi], v[lo:hi])
+        oracle.opt_undo(oh, sx, g[lo:hi], sm, sv)
+        for a in (x32, m32, v32):
+            oracle.digest(a[lo:hi])
+
+    best = None
+    with cf.ThreadPoolExecutor(cores) as pool:
+        for _ in range(3):                       # first round also warms the allocator's pages
+            t0 = time.perf_counter()
+            list(pool.map(work, range(cores)))
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+    n1 = n // cores
+    t0 = time.perf_counter()
+    sx, sm, sv = oracle.opt_step(oh, x[:n1], g[:n1], m[:n1], v[:n1])
+    oracle.opt_undo(oh, sx, g[:n1], sm, sv)
+    t1 = time.perf_counter() - t0
+    return {"value": 2 * n / best, "unit": "params/s", "cores": cores, "kind": "oracle",
+            "sample": f"AdamW step+undo and 3 digests on the first {n} elements of tensor 0 of {w.name}, "
+                      f"static split over {cores} threads, best of 3",
+            "single_thread_value": 2 * n1 / t1}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b_adamw")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=128 * 1024 * 1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU: the update-undo path needs no communication, every replica "
+            "undoes its own copy.  Run with --gpus 1.")
+        return 2
+
+    import torch
+    from paper_2302_06173_amd import binding as B, synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 2
+    torch.cuda.set_device(0)
+    w = synth.workloads()[args.workload]
+    N, n_t = w.n_params, len(w.shapes)
+    log(f"[bench] workload {w.name}: {n_t} tensors, {N:,} params; drawing state on the GPU ...")
+    t0 = time.perf_counter()
+    state = synth.make_state(w, "cuda:0", with_v=True)
+    torch.cuda.synchronize()
+    log(f"[bench] state ready in {time.perf_counter() - t0:.1f} s; "
+        f"{torch.cuda.memory_allocated() / 1e9:.1f} GB allocated")
+
+    bf16 = w.grad_bf16
+    own = dict(w.hyper)
+    t_step = own.get("step", 1)
+    hp_dicts = {
+        "adamw": dict(lr=6e-4, weight_decay=0.1, beta1=0.9, beta2=0.95, eps=1e-8, step=t_step),
+        "adam": dict(lr=1e-3, weight_decay=0.0, beta1=0.9, beta2=0.999, eps=1e-8, step=t_step),
+        "sgdm": dict(lr=0.1, weight_decay=1e-4, momentum=0.9, dampening=0.0, step=t_step),
+    }
+    hp_dicts[w.kind] = {**hp_dicts[w.kind], **own}
+    hps = {k: B.hparams(k, grad_bf16=bf16, **d) for k, d in hp_dicts.items()}
+    tl_adam = B.TensorList(state.theta, state.grad, state.m, state.v)
+    tl_sgdm = B.TensorList(state.theta, state.grad, state.m, None)
+    bufs = B.BufferList(state.theta + state.m + state.v)
+    frac = w.masked_fraction if w.masked_fraction > 0 else 0.5
+    wm = synth.Workload(**{**w.__dict__, "masked_fraction": frac})
+    mask = synth.tensor_mask(wm, n_t)
+    n_masked = sum(synth.numel(s) for s, b in zip(w.shapes, mask) if b)
+    n_digests = B.swift_digest_count([t.numel() for t in bufs._keep], 0)
+    d0 = torch.empty(n_digests, dtype=torch.int64, device="cuda")
+    d1 = torch.empty_like(d0)
+    dmask = torch.empty(n_t, dtype=torch.uint8, device="cuda")
+
+    segs = ["digest_pre", "adamw_step_masked", "digest_post", "mask_from_digests", "adamw_undo_selective",
+            "adamw_step", "adamw_undo", "adam_step", "adam_undo", "sgdm_step", "sgdm_undo"]
+    g_bytes = 2 if bf16 else 4
+    seg_bytes = {"digest_pre": 12 * N, "digest_post": 12 * N, "mask_from_digests": 0,
+                 "adamw_step_masked": (24 + g_bytes) * n_masked, "adamw_undo_selective": (24 + g_bytes) * n_masked,
+                 "adamw_step": (24 + g_bytes) * N, "adamw_undo": (24 + g_bytes) * N,
+                 "adam_step": (24 + g_bytes) * N, "adam_undo": (24 + g_bytes) * N,
+                 "sgdm_step": (16 + g_bytes) * N, "sgdm_undo": (16 + g_bytes) * N}
+    seg_params = {s: 0 for s in segs}
+    seg_params.update({"adamw_step_masked": n_masked, "adamw_undo_selective": n_masked, "adamw_step": N,
+                       "adamw_undo": N, "adam_step": N, "adam_undo": N, "sgdm_step": N, "sgdm_undo": N})
+
+    def one_pass(events=None):
+        def mark():
+            if events is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                events.append(e)
+        mark()
+        B.swift_state_digest(bufs, 0, out=d0); mark()
+        B.swift_opt_step(tl_adam, hps["adamw"], host_mask=mask); mark()
+        B.swift_state_digest(bufs, 0, out=d1); mark()
+        B.swift_mask_from_digests(d0, d1, n_t, out=dmask); mark()
+        B.swift_opt_undo_dmask(tl_adam, hps["adamw"], dmask); mark()
+        B.swift_opt_step(tl_adam, hps["adamw"]); mark()
+        B.swift_opt_undo(tl_adam, hps["adamw"]); mark()
+        B.swift_opt_step(tl_adam, hps["adam"]); mark()
+        B.swift_opt_undo(tl_adam, hps["adam"]); mark()
+        B.swift_opt_step(tl_sgdm, hps["sgdm"]); mark()
+        B.swift_opt_undo(tl_sgdm, hps["sgdm"]); mark()
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    if dmask.cpu().tolist() != [1 if (b and synth.numel(s)) else 0 for b, s in zip(mask, w.shapes)]:
+        log("[bench] ERROR: digest-derived mask differs from the step mask")
+        return 1
+    all_events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev = []
+        one_pass(ev)
+        all_events.append(ev)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    seg_ms = {s: 0.0 for s in segs}
+    for ev in all_events:
+        for k, s in enumerate(segs):
+            seg_ms[s] += ev[k].elapsed_time(ev[k + 1])
+    seg_ms = {s: v / max(args.steps, 1) for s, v in seg_ms.items()}
+    params_per_pass = sum(seg_params.values())
+    value = params_per_pass * args.steps / wall
+    kernels = {}
+    for s in segs:
+        ms = seg_ms[s]
+        kernels[s] = {"ms": round(ms, 4), "gparams_per_s": round(seg_params[s] / ms / 1e6, 2) if ms > 0 else None,
+                      "gb_per_s": round(seg_bytes[s] / ms / 1e6, 1) if ms > 0 else None}
+        log(f"[bench] {s:22s} {ms:9.3f} ms  {kernels[s]['gparams_per_s']} Gparam/s  {kernels[s]['gb_per_s']} GB/s")
+    # The AdamW undo kernel is launched twice per pass (selective undo of the marked half, then the
+    # full list); a profiler averages over both, so the roofline figure does too.
+    dom = ("adamw_undo_selective", "adamw_undo")
+    dom_bytes = sum(seg_bytes[s] for s in dom) / len(dom)
+    dom_ms = sum(seg_ms[s] for s in dom) / len(dom)
+    dom_params = sum(seg_params[s] for s in dom) / len(dom)
+    achieved = dom_bytes / dom_ms / 1e6
+    traffic = measured_traffic(w.name)
+    out = {
+        "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * wall / max(args.steps, 1), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {n_t} tensors, {N} params, fp32 theta/m/v, "
+                               f"{'bf16' if bf16 else 'fp32'} grads, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident",
+                   "pass": "digest, masked AdamW step, digest, mask, selective undo, full AdamW/Adam/SGDM step+undo",
+                   "params_updated_or_undone_per_pass": params_per_pass,
+                   "storage": "fp32 state, arithmetic in fp64 registers"},
+        "roofline": {"bound": "hbm", "kernel": "opt_kernel<AdamW, undo>: mean of its 2 launches per pass "
+                                                 "(selective undo of the marked tensors, full list)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
+                     "gparams_per_s": dom_params / dom_ms / 1e6},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(w, state, hp_dicts["adamw"], args.cpu_sample)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
