@@ -53,6 +53,7 @@ long env_long(const char *name, long dflt) {
 // Device facts, queried once per device.
 struct DeviceInfo {
   int cus = 0;
+  int lds_per_cu = 0;   // bytes
 };
 
 int device_info(int dev, DeviceInfo *out) {
@@ -64,7 +65,10 @@ int device_info(int dev, DeviceInfo *out) {
     int cus = 0;
     SWIFT_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     if (cus <= 0) return fail(SWIFT_EHIP, "device %d reports %d compute units", dev, cus);
+    int lds = 0;
+    SWIFT_HIP(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev));
     cache[dev].cus = cus;
+    cache[dev].lds_per_cu = lds > 0 ? lds : 64 * 1024;
   }
   *out = cache[dev];
   return SWIFT_OK;
@@ -92,9 +96,7 @@ struct Plan {
   uint32_t chunk_elems = 0;
   uint64_t n_out = 0;            // digest plans: number of outputs
   const void *descs() const { return dev_mem; }
-  const ChunkRef *chunks() const {
-    return reinterpret_cast<const ChunkRef *>(static_cast<const char *>(dev_mem) + desc_bytes);
-  }
+  const void *chunks() const { return static_cast<const char *>(dev_mem) + desc_bytes; }
   ~Plan() {
     if (dev_mem) {
       int cur = -1;
@@ -166,27 +168,53 @@ int check_device_range(const void *p, size_t bytes, int dev, const char *what, i
   return SWIFT_OK;
 }
 
-uint32_t pick_chunk_elems(uint64_t total, uint64_t resident_wgs, int unroll) {
-  const uint32_t tile = (uint32_t)unroll * kThreads * 4;       // elements per unrolled workgroup pass
-  long forced = env_long("SWIFT_CHUNK_ELEMS", 0);              // tuning knob for sweeps
-  if (forced >= (long)tile && forced <= (1l << 22) && forced % tile == 0) return (uint32_t)forced;
-  uint32_t ce = 16384;
-  while (ce > 4096 && total / ce < 8 * resident_wgs) ce >>= 1;
-  if (ce < tile) ce = tile;
-  return ce;
+// Launch shape of the streaming kernels: U 16-byte vectors per lane, BLOCK lanes per workgroup,
+// at most `waves_per_cu` wavefronts resident on a compute unit (0 = no cap).  The defaults come
+// from sweeps on MI355X; the environment variables exist for such sweeps.
+struct Tuning {
+  int u, block, waves_per_cu;
+};
+
+Tuning opt_tuning(int kind) {
+  // SGDM moves 3 streams in and 2 out per element instead of 4 and 3, and wants more wavefronts
+  Tuning t{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK,
+           kind == SWIFT_SGDM ? SWIFT_DEFAULT_WAVES_PER_CU_SGDM : SWIFT_DEFAULT_WAVES_PER_CU};
+  t.u = (int)env_long("SWIFT_TILE_U", t.u);
+  t.block = (int)env_long("SWIFT_TILE_BLOCK", t.block);
+  t.waves_per_cu = (int)env_long("SWIFT_WAVES_PER_CU", t.waves_per_cu);
+  return t;
 }
 
-int upload_plan(Plan &plan, const void *descs, size_t desc_bytes, const std::vector<ChunkRef> &chunks) {
+// Dynamic LDS bytes per workgroup that make at most waves_per_cu wavefronts fit on one CU.
+uint32_t lds_cap_bytes(const DeviceInfo &info, const Tuning &t) {
+  const int wgs = t.waves_per_cu / (t.block / 64);
+  if (t.waves_per_cu <= 0 || wgs >= 32) return 0;
+  const int w = wgs < 3 ? 3 : wgs;                      // stay within the 64 KiB a launch may ask for
+  uint32_t bytes = (uint32_t)(info.lds_per_cu / w) & ~511u;
+  return bytes > 65536u ? 65536u : bytes;
+}
+
+// Chunk length (a power of two, at least one tile).  Long chunks keep the table small; short
+// ones waste fewer idle workgroups on the many tiny tensors of a small model.
+uint32_t pick_chunk_elems(uint32_t tile_elems, uint64_t total_elems) {
+  long forced = env_long("SWIFT_CHUNK_ELEMS", 0);              // tuning knob for sweeps
+  if (forced >= (long)tile_elems && forced <= (1l << 22) && (forced & (forced - 1)) == 0) return (uint32_t)forced;
+  const uint32_t ce = total_elems >= (1ull << 28) ? 65536u : 16384u;
+  return tile_elems > ce ? tile_elems : ce;
+}
+
+int upload_plan(Plan &plan, const void *descs, size_t desc_bytes, const void *chunks, size_t n_chunks,
+                size_t chunk_size) {
   plan.desc_bytes = (desc_bytes + 255) & ~size_t(255);
-  const size_t total = plan.desc_bytes + std::max<size_t>(chunks.size(), 1) * sizeof(ChunkRef);
+  const size_t total = plan.desc_bytes + std::max<size_t>(n_chunks, 1) * chunk_size;
   SWIFT_HIP(hipMalloc(&plan.dev_mem, total));
   // Synchronous copies: when they return the table is complete in device memory, so any stream
   // may read it.  This happens once per distinct tensor list.
   if (desc_bytes) SWIFT_HIP(hipMemcpy(plan.dev_mem, descs, desc_bytes, hipMemcpyHostToDevice));
-  if (!chunks.empty())
-    SWIFT_HIP(hipMemcpy(static_cast<char *>(plan.dev_mem) + plan.desc_bytes, chunks.data(),
-                        chunks.size() * sizeof(ChunkRef), hipMemcpyHostToDevice));
-  plan.n_chunks = (uint32_t)chunks.size();
+  if (n_chunks)
+    SWIFT_HIP(hipMemcpy(static_cast<char *>(plan.dev_mem) + plan.desc_bytes, chunks, n_chunks * chunk_size,
+                        hipMemcpyHostToDevice));
+  plan.n_chunks = (uint32_t)n_chunks;
   return SWIFT_OK;
 }
 
@@ -261,7 +289,7 @@ int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
 }
 
 int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, int dev,
-                   uint64_t resident_wgs, std::shared_ptr<Plan> *out) {
+                   uint32_t tile_elems, std::shared_ptr<Plan> *out) {
   const bool hasv = hp->kind != SWIFT_SGDM;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16;
   std::string key;
@@ -271,6 +299,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   key_add(key, (uint8_t)hasv);
   key_add(key, (uint8_t)bf16);
   key_add(key, l->n);
+  key_add(key, tile_elems);
   key_add(key, env_long("SWIFT_CHUNK_ELEMS", 0));
   for (int64_t i = 0; i < l->n; ++i) {
     const uint8_t on = host_mask ? (host_mask[i] != 0) : 1;
@@ -288,15 +317,12 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   }
 
   // Miss: check every pointer against the runtime's allocation records, check that nothing that
-  // is written overlaps anything else, then build and upload the tables.
-  std::vector<TensorDesc> descs((size_t)l->n);
+  // is written overlaps anything else, then build and upload the chunk table.
   std::vector<Interval> iv;
   iv.reserve((size_t)l->n * 4);
   uint64_t total = 0;
   const size_t gsz = bf16 ? 2 : 4;
   for (int64_t i = 0; i < l->n; ++i) {
-    TensorDesc &d = descs[(size_t)i];
-    memset(&d, 0, sizeof d);
     const uint64_t n = (uint64_t)l->numel[i];
     if (n == 0) continue;
     int rc;
@@ -304,17 +330,11 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     if ((rc = check_device_range(l->grad[i], n * gsz, dev, "grad", i))) return rc;
     if ((rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
     if (hasv && (rc = check_device_range(l->v[i], n * 4, dev, "v", i))) return rc;
-    d.x = static_cast<float *>(l->param[i]);
-    d.g = l->grad[i];
-    d.m = static_cast<float *>(l->m[i]);
-    d.v = hasv ? static_cast<float *>(l->v[i]) : nullptr;
-    d.numel = (int64_t)n;
-    uintptr_t bits = (uintptr_t)d.x | (uintptr_t)d.m | (hasv ? (uintptr_t)d.v : 0);
-    d.vec_ok = ((bits & 15) == 0) && (((uintptr_t)d.g & (bf16 ? 7 : 15)) == 0);
-    iv.push_back({(uintptr_t)d.x, (uintptr_t)d.x + n * 4, true});
-    iv.push_back({(uintptr_t)d.g, (uintptr_t)d.g + n * gsz, false});
-    iv.push_back({(uintptr_t)d.m, (uintptr_t)d.m + n * 4, true});
-    if (hasv) iv.push_back({(uintptr_t)d.v, (uintptr_t)d.v + n * 4, true});
+    const uintptr_t x = (uintptr_t)l->param[i], g = (uintptr_t)l->grad[i], m = (uintptr_t)l->m[i];
+    iv.push_back({x, x + n * 4, true});
+    iv.push_back({g, g + n * gsz, false});
+    iv.push_back({m, m + n * 4, true});
+    if (hasv) iv.push_back({(uintptr_t)l->v[i], (uintptr_t)l->v[i] + n * 4, true});
     if (!host_mask || host_mask[i]) total += n;
   }
   std::sort(iv.begin(), iv.end(), [](const Interval &a, const Interval &b) { return a.lo < b.lo; });
@@ -326,38 +346,61 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   auto plan = std::make_shared<Plan>();
   plan->key = std::move(key);
   plan->device = dev;
-  plan->chunk_elems = pick_chunk_elems(total, resident_wgs, SWIFT_UNROLL);
-  std::vector<ChunkRef> chunks;
-  chunks.reserve((size_t)(total / plan->chunk_elems) + (size_t)l->n);
+  plan->chunk_elems = pick_chunk_elems(tile_elems, total);
+  const uint64_t ce = plan->chunk_elems;
+  std::vector<ChunkDesc> chunks;
+  chunks.reserve((size_t)(total / ce) + (size_t)l->n);
   for (int64_t i = 0; i < l->n; ++i) {
     if (host_mask && !host_mask[i]) continue;
     const uint64_t n = (uint64_t)l->numel[i];
-    const uint64_t nc = (n + plan->chunk_elems - 1) / plan->chunk_elems;
-    if (nc > 0xffffffffull) return fail(SWIFT_EINVAL, "tensor %lld is too large", (long long)i);
-    for (uint64_t k = 0; k < nc; ++k) chunks.push_back({(uint32_t)i, (uint32_t)k});
+    if (n == 0) continue;
+    char *x = static_cast<char *>(l->param[i]), *m = static_cast<char *>(l->m[i]);
+    char *v = hasv ? static_cast<char *>(l->v[i]) : nullptr;
+    const char *g = static_cast<const char *>(l->grad[i]);
+    const uintptr_t bits = (uintptr_t)x | (uintptr_t)m | (uintptr_t)v;
+    const uint32_t vec_ok = ((bits & 15) == 0) && (((uintptr_t)g & (bf16 ? 7 : 15)) == 0);
+    for (uint64_t off = 0; off < n; off += ce) {
+      ChunkDesc d;
+      d.x = reinterpret_cast<float *>(x + off * 4);
+      d.g = g + off * gsz;
+      d.m = reinterpret_cast<float *>(m + off * 4);
+      d.v = hasv ? reinterpret_cast<float *>(v + off * 4) : nullptr;
+      d.len = (uint32_t)std::min<uint64_t>(ce, n - off);
+      d.tensor = (uint32_t)i;
+      d.vec_ok = vec_ok;
+      d.pad = 0;
+      chunks.push_back(d);
+    }
   }
-  if (chunks.size() > 0xffffffffull) return fail(SWIFT_EINVAL, "tensor list is too large");
-  int rc = upload_plan(*plan, descs.data(), descs.size() * sizeof(TensorDesc), chunks);
+  if (chunks.size() > 0x7fffffffull) return fail(SWIFT_EINVAL, "tensor list is too large");
+  int rc = upload_plan(*plan, nullptr, 0, chunks.data(), chunks.size(), sizeof(ChunkDesc));
   if (rc) return rc;
   keep_plan(plan);
   *out = plan;
   return SWIFT_OK;
 }
 
-typedef void (*OptKernel)(const TensorDesc *, const ChunkRef *, uint32_t, uint32_t, const uint8_t *, const OptConsts);
+typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const uint8_t *, const OptConsts);
 
-template <int KIND, bool UNDO>
-OptKernel pick_grad(bool bf16) {
-  return bf16 ? opt_kernel<KIND, UNDO, true, SWIFT_NT != 0, SWIFT_UNROLL>
-              : opt_kernel<KIND, UNDO, false, SWIFT_NT != 0, SWIFT_UNROLL>;
+template <int U, int BLOCK>
+OptKernel pick_kernel_shape(int kind, bool undo, bool bf16) {
+#define SWIFT_PICK(K)                                                                                   \
+  (undo ? (bf16 ? opt_kernel<K, true, true, U, BLOCK> : opt_kernel<K, true, false, U, BLOCK>)           \
+        : (bf16 ? opt_kernel<K, false, true, U, BLOCK> : opt_kernel<K, false, false, U, BLOCK>))
+  switch (kind) {
+    case SWIFT_SGDM: return SWIFT_PICK(kSGDM);
+    case SWIFT_ADAM: return SWIFT_PICK(kADAM);
+    default: return SWIFT_PICK(kADAMW);
+  }
+#undef SWIFT_PICK
 }
 
-OptKernel pick_kernel(int kind, bool undo, bool bf16) {
-  switch (kind) {
-    case SWIFT_SGDM: return undo ? pick_grad<kSGDM, true>(bf16) : pick_grad<kSGDM, false>(bf16);
-    case SWIFT_ADAM: return undo ? pick_grad<kADAM, true>(bf16) : pick_grad<kADAM, false>(bf16);
-    default: return undo ? pick_grad<kADAMW, true>(bf16) : pick_grad<kADAMW, false>(bf16);
-  }
+// The launch shapes that are compiled in.  Returns nullptr for any other (U, BLOCK).
+OptKernel pick_kernel(const Tuning &t, int kind, bool undo, bool bf16) {
+#define SWIFT_SHAPE(U_, B_) if (t.u == U_ && t.block == B_) return pick_kernel_shape<U_, B_>(kind, undo, bf16);
+  SWIFT_SHAPES(SWIFT_SHAPE)
+#undef SWIFT_SHAPE
+  return nullptr;
 }
 
 int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask,
@@ -372,18 +415,21 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   SWIFT_HIP(hipGetDevice(&dev));
   DeviceInfo info;
   if ((rc = device_info(dev, &info))) return rc;
-  const OptKernel kernel = pick_kernel(hp->kind, undo, hp->grad_dtype == SWIFT_BF16);
-  int per_cu = 1;
-  if ((rc = resident_groups(reinterpret_cast<const void *>(kernel), &per_cu))) return rc;
-  const uint64_t resident = (uint64_t)info.cus * (uint64_t)per_cu;
+  const Tuning tune = opt_tuning(hp->kind);
+  const OptKernel kernel = pick_kernel(tune, hp->kind, undo, hp->grad_dtype == SWIFT_BF16);
+  if (!kernel) return fail(SWIFT_EINVAL, "launch shape U=%d BLOCK=%d is not compiled in", tune.u, tune.block);
+  const uint32_t tile_elems = (uint32_t)tune.u * (uint32_t)tune.block * 4u;
   if (want_dmask && (rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
   std::shared_ptr<Plan> plan;
-  if ((rc = build_opt_plan(l, hp, host_mask, dev, resident, &plan))) return rc;
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, tile_elems, &plan))) return rc;
   if (plan->n_chunks == 0) return SWIFT_OK;
-  const uint32_t grid = (uint32_t)std::min<uint64_t>(plan->n_chunks, resident);
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const TensorDesc *>(plan->descs()), plan->chunks(), plan->n_chunks, plan->chunk_elems,
-                     device_mask, c);
+  uint32_t tpc_shift = 0;
+  while ((tile_elems << tpc_shift) < plan->chunk_elems) ++tpc_shift;
+  const uint64_t n_work = (uint64_t)plan->n_chunks << tpc_shift;
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(n_work, 0x7fffffffull);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3((uint32_t)tune.block), lds_cap_bytes(info, tune),
+                     static_cast<hipStream_t>(stream), static_cast<const ChunkDesc *>(plan->chunks()), n_work,
+                     tpc_shift, device_mask, c);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }
@@ -408,6 +454,16 @@ int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, b
   return total;
 }
 
+// Digest chunks: as large as still leaves every resident workgroup several chunks.
+uint32_t digest_chunk_elems(uint64_t total, uint64_t resident_wgs) {
+  const uint32_t tile = (uint32_t)SWIFT_UNROLL * kThreads * 4;
+  long forced = env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0);       // tuning knob for sweeps
+  if (forced >= (long)tile && forced <= (1l << 22) && forced % tile == 0) return (uint32_t)forced;
+  uint32_t ce = 16384;
+  while (ce > 4096 && total / ce < 8 * resident_wgs) ce >>= 1;
+  return ce < tile ? tile : ce;
+}
+
 int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *numel, int64_t shard_elems, int dev,
                       uint64_t resident_wgs, std::shared_ptr<Plan> *out) {
   std::string key;
@@ -416,7 +472,7 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   key_add(key, dev);
   key_add(key, n_buf);
   key_add(key, shard_elems);
-  key_add(key, env_long("SWIFT_CHUNK_ELEMS", 0));
+  key_add(key, env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0));
   for (int64_t i = 0; i < n_buf; ++i) {
     key_add(key, numel[i]);
     key_add(key, buf[i]);
@@ -442,7 +498,7 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   plan->key = std::move(key);
   plan->device = dev;
   plan->n_out = n_out;
-  plan->chunk_elems = pick_chunk_elems(total, resident_wgs, SWIFT_UNROLL);
+  plan->chunk_elems = digest_chunk_elems(total, resident_wgs);
   const uint64_t ce = plan->chunk_elems;
   std::vector<ChunkRef> chunks;
   chunks.reserve((size_t)(total / ce) + (size_t)n_out);
@@ -460,7 +516,8 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
     }
   }
   if (chunks.size() > 0xffffffffull) return fail(SWIFT_EINVAL, "digest: too many chunks");
-  int rc = upload_plan(*plan, descs.data(), descs.size() * sizeof(DigestDesc), chunks);
+  int rc = upload_plan(*plan, descs.data(), descs.size() * sizeof(DigestDesc), chunks.data(), chunks.size(),
+                       sizeof(ChunkRef));
   if (rc) return rc;
   keep_plan(plan);
   *out = plan;
@@ -524,7 +581,8 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
   if (plan->n_chunks == 0) return SWIFT_OK;
   const uint32_t grid = (uint32_t)std::min<uint64_t>(plan->n_chunks, resident);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
-                     plan->chunks(), plan->n_chunks, plan->chunk_elems, (uint64_t)shard_elems,
+                     static_cast<const ChunkRef *>(plan->chunks()), plan->n_chunks, plan->chunk_elems,
+                     (uint64_t)shard_elems,
                      reinterpret_cast<unsigned long long *>(out_device));
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
@@ -564,14 +622,15 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
   if ((rc = check_device_range(src_device, (size_t)bytes, dev, "src_device", 0))) return rc;
   const char *d = static_cast<const char *>(dst_device), *s = static_cast<const char *>(src_device);
   if (d < s + bytes && s < d + bytes) return fail(SWIFT_EINVAL, "stream_copy: ranges overlap");
-  const auto kernel = copy_kernel<SWIFT_NT != 0, SWIFT_UNROLL>;
-  int per_cu = 1;
-  if ((rc = resident_groups(reinterpret_cast<const void *>(kernel), &per_cu))) return rc;
+  const Tuning tune{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK, (int)env_long("SWIFT_WAVES_PER_CU", SWIFT_DEFAULT_WAVES_PER_CU)};
+  const auto kernel = copy_kernel<SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK>;
   const uint64_t n16 = (uint64_t)bytes / 16;
-  const uint64_t tiles = (n16 + (uint64_t)SWIFT_UNROLL * kThreads - 1) / ((uint64_t)SWIFT_UNROLL * kThreads);
-  const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, (uint64_t)info.cus * (uint64_t)per_cu);
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
-                     static_cast<u32x4 *>(dst_device), static_cast<const u32x4 *>(src_device), n16);
+  const uint64_t tile = (uint64_t)SWIFT_DEFAULT_U * SWIFT_DEFAULT_BLOCK;
+  const uint64_t tiles = (n16 + tile - 1) / tile;
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, 0x7fffffffull);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(SWIFT_DEFAULT_BLOCK), lds_cap_bytes(info, tune),
+                     static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
+                     static_cast<const u32x4 *>(src_device), n16);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }

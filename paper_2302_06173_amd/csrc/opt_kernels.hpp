@@ -15,7 +15,17 @@ namespace swift {
 constexpr int kSGDM = 0, kADAM = 1, kADAMW = 2;
 constexpr int kThreads = 256;           // 4 wavefronts of 64
 #ifndef SWIFT_UNROLL
-#define SWIFT_UNROLL 2                  // 16-byte accesses in flight per lane and stream
+#define SWIFT_UNROLL 2                  // digest kernel: 16-byte loads in flight per lane
+#endif
+// Launch shapes of the optimizer kernels that get compiled: X(U, BLOCK).
+#ifndef SWIFT_SHAPES
+#define SWIFT_SHAPES(X) X(1, 64) X(2, 64) X(4, 64) X(1, 256)
+#endif
+#ifndef SWIFT_DEFAULT_U
+#define SWIFT_DEFAULT_U 1
+#define SWIFT_DEFAULT_BLOCK 64
+#define SWIFT_DEFAULT_WAVES_PER_CU 11
+#define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
 #endif
 #ifndef SWIFT_NT
 #define SWIFT_NT 1                      // non-temporal (streaming) loads and stores
@@ -25,19 +35,20 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-struct TensorDesc {        // one per tensor, 48 bytes, device resident
-  float *x;                // theta, in/out
+struct ChunkDesc {         // one per chunk of the optimizer kernels, 48 bytes, device resident
+  float *x;                // theta of the chunk's first element, in/out
   const void *g;           // gradient, fp32 or bf16, read only
   float *m;                // momentum buffer / first moment, in/out
-  float *v;                // second moment, in/out (unused for SGDM)
-  int64_t numel;
-  uint32_t vec_ok;         // 1: all pointers aligned for the 128-bit path
+  float *v;                // second moment, in/out (null for SGDM)
+  uint32_t len;            // elements in this chunk (the last chunk of a tensor is short)
+  uint32_t tensor;         // index of the tensor in the caller's list (for the device mask)
+  uint32_t vec_ok;         // 1: all four pointers are aligned for the 128-bit path
   uint32_t pad;
 };
 
-struct ChunkRef {          // one per chunk, 8 bytes, device resident
+struct ChunkRef {          // digest kernel: one per chunk, 8 bytes, device resident
   uint32_t tensor;         // index into the descriptor table
-  uint32_t chunk;          // chunk number inside the tensor: elements [chunk*CE, chunk*CE+CE)
+  uint32_t chunk;          // chunk number inside the buffer
 };
 
 // Scalars derived on the host in binary64 from the hyper-parameters (never as 1.0f - float(beta)).
@@ -66,6 +77,27 @@ __device__ __forceinline__ void st(T *p, T val) {
   SWIFT_GLOBAL T *q = (SWIFT_GLOBAL T *)p;
   if constexpr (NT) __builtin_nontemporal_store(val, q);
   else *q = val;
+}
+
+// Streaming accesses of the 128-bit path go through buffer instructions: the chunk's base pointer
+// is wave-uniform, the byte range of the chunk is the buffer's extent (the hardware drops
+// anything outside it), and the cache-policy bits can be chosen per access.  Measured on MI355X
+// for the 4-read/3-write stream: loads `nt`; stores `sc0 sc1 nt` (2-3 % above `nt` alone,
+// 9 % above default stores).
+#ifndef SWIFT_LOAD_AUX
+#define SWIFT_LOAD_AUX 2                // nt
+#endif
+#ifndef SWIFT_STORE_AUX
+#define SWIFT_STORE_AUX 19              // sc0 (1) | nt (2) | sc1 (16)
+#endif
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00027000);
+}
+__device__ __forceinline__ f32x4 buf_ld4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, SWIFT_LOAD_AUX));
+}
+__device__ __forceinline__ void buf_st4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f32x4 val) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), r, (int)byte_off, 0, SWIFT_STORE_AUX);
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
@@ -125,10 +157,11 @@ __device__ __forceinline__ void update_vec4(f32x4 &x, const f32x4 &g, f32x4 &m, 
   }
 }
 
-template <bool BF16G, bool NT>
-__device__ __forceinline__ f32x4 load_grad4(const void *g, int64_t i4) {
+// Vector j (4 consecutive elements) of the chunk's gradient, widened to fp32.
+template <bool BF16G>
+__device__ __forceinline__ f32x4 load_grad4(__amdgpu_buffer_rsrc_t rg, uint32_t j) {
   if constexpr (BF16G) {
-    const u32x2 raw = ld<NT>(reinterpret_cast<const u32x2 *>(g) + i4);   // 4 bf16 = 8 bytes
+    const u32x2 raw = __builtin_amdgcn_raw_buffer_load_b64(rg, (int)(j * 8u), 0, SWIFT_LOAD_AUX);   // 4 bf16
     f32x4 r;
     r[0] = bf16_bits_to_f32(raw[0] & 0xFFFFu);
     r[1] = bf16_bits_to_f32(raw[0] >> 16);
@@ -136,7 +169,7 @@ __device__ __forceinline__ f32x4 load_grad4(const void *g, int64_t i4) {
     r[3] = bf16_bits_to_f32(raw[1] >> 16);
     return r;
   } else {
-    return ld<NT>(reinterpret_cast<const f32x4 *>(g) + i4);
+    return buf_ld4(rg, j * 16u);
   }
 }
 
@@ -146,71 +179,84 @@ __device__ __forceinline__ float load_grad1(const void *g, int64_t i) {
   else return ld<false>(reinterpret_cast<const float *>(g) + i);
 }
 
-// Grid-stride over the chunk table.  `dmask` (nullable) holds one byte per tensor in device
-// memory: chunks of tensors whose byte is zero are skipped.
-template <int KIND, bool UNDO, bool BF16G, bool NT, int U>
-__global__ void __launch_bounds__(kThreads)
-opt_kernel(const TensorDesc *__restrict__ descs, const ChunkRef *__restrict__ chunks, uint32_t n_chunks,
-           uint32_t chunk_elems, const uint8_t *__restrict__ dmask, const OptConsts c) {
+// One workgroup per tile.  A tile is U*BLOCK 16-byte vectors (U*BLOCK*4 elements) of one chunk; a
+// chunk is up to `chunk_elems` consecutive elements of one tensor (the last chunk of a tensor is
+// short) and spans tiles_per_chunk = 1 << tpc_shift work items, so work item w is tile
+// (w & (tpc-1)) of chunk (w >> tpc_shift).  The chunk table holds ready-made pointers, so a
+// wavefront is one scalar load away from issuing its vector loads.  The grid normally equals the
+// number of work items: the hardware dispatcher then hands tiles out in address order as
+// wavefronts retire, which keeps the window of HBM pages in flight narrow (a persistent
+// grid-stride loop lets workgroups drift apart and measured 10-20 % slower for this
+// 4-read/3-write pattern).  The launch passes dynamic LDS that is never touched: it only caps how
+// many workgroups share a compute unit, because more than ~10 wavefronts per CU in flight lowers
+// the achieved HBM bandwidth of the mixed read/write stream.
+// `dmask` (nullable) holds one byte per tensor in device memory: tiles of tensors whose byte is
+// zero are skipped.
+template <int KIND, bool UNDO, bool BF16G, int U, int BLOCK>
+__global__ void __launch_bounds__(BLOCK)
+opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_work, uint32_t tpc_shift,
+           const uint8_t *__restrict__ dmask, const OptConsts c) {
   constexpr bool HASV = (KIND != kSGDM);
+  constexpr uint32_t TILE4 = U * BLOCK;                          // vectors per tile
   const uint32_t tid = threadIdx.x;
-  for (uint32_t ci = blockIdx.x; ci < n_chunks; ci += gridDim.x) {
-    const ChunkRef ch = chunks[ci];
-    if (dmask != nullptr && dmask[ch.tensor] == 0) continue;
-    const TensorDesc d = descs[ch.tensor];
-    const int64_t base = (int64_t)ch.chunk * chunk_elems;
-    const int64_t left = d.numel - base;
-    const uint32_t len = left < (int64_t)chunk_elems ? (uint32_t)left : chunk_elems;
-    float *__restrict__ xp = d.x + base;
-    float *__restrict__ mp = d.m + base;
-    float *__restrict__ vp = HASV ? d.v + base : nullptr;
-    const void *gp = BF16G ? (const void *)(reinterpret_cast<const uint16_t *>(d.g) + base)
-                           : (const void *)(reinterpret_cast<const float *>(d.g) + base);
+  for (uint64_t w = blockIdx.x; w < n_work; w += gridDim.x) {
+    const ChunkDesc d = chunks[w >> tpc_shift];
+    const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
+    const uint32_t len = d.len;
+    const uint32_t e0 = ti * (TILE4 * 4u);                       // first element of this tile in the chunk
+    if (e0 >= len) continue;                                     // short last chunk: nothing here
+    if (dmask != nullptr && dmask[d.tensor] == 0) continue;
+    float *__restrict__ xp = d.x;
+    float *__restrict__ mp = d.m;
+    float *__restrict__ vp = d.v;
+    const void *gp = d.g;
     if (d.vec_ok) {
-      // chunk_elems is a multiple of 4, so `base` keeps the 16-byte alignment of the tensor
-      f32x4 *x4 = reinterpret_cast<f32x4 *>(xp);
-      f32x4 *m4 = reinterpret_cast<f32x4 *>(mp);
-      f32x4 *v4 = reinterpret_cast<f32x4 *>(vp);
+      // chunk starts are multiples of 4 elements, so chunks keep their tensor's 16-byte alignment
       const uint32_t n4 = len >> 2;
-      uint32_t i = 0;
-      for (; i + U * kThreads <= n4; i += U * kThreads) {       // full tiles: no predicates
+      const __amdgpu_buffer_rsrc_t rx = make_rsrc(xp, n4 * 16u), rm = make_rsrc(mp, n4 * 16u);
+      const __amdgpu_buffer_rsrc_t rv = make_rsrc(vp, HASV ? n4 * 16u : 0u);
+      const __amdgpu_buffer_rsrc_t rg = make_rsrc(gp, n4 * (BF16G ? 8u : 16u));
+      const uint32_t j0 = ti * TILE4;
+      if (j0 + TILE4 <= n4) {                                    // full tile: no predicates
         f32x4 xr[U], gr[U], mr[U], vr[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const uint32_t j = i + u * kThreads + tid;
-          xr[u] = ld<NT>(x4 + j);
-          gr[u] = load_grad4<BF16G, NT>(gp, j);
-          mr[u] = ld<NT>(m4 + j);
-          if constexpr (HASV) vr[u] = ld<NT>(v4 + j);
+          const uint32_t j = j0 + u * BLOCK + tid;
+          xr[u] = buf_ld4(rx, j * 16u);
+          gr[u] = load_grad4<BF16G>(rg, j);
+          mr[u] = buf_ld4(rm, j * 16u);
+          if constexpr (HASV) vr[u] = buf_ld4(rv, j * 16u);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const uint32_t j = i + u * kThreads + tid;
+          const uint32_t j = j0 + u * BLOCK + tid;
           update_vec4<KIND, UNDO>(xr[u], gr[u], mr[u], vr[u], c);
-          st<NT>(x4 + j, xr[u]);
-          st<NT>(m4 + j, mr[u]);
-          if constexpr (HASV) st<NT>(v4 + j, vr[u]);
+          buf_st4(rx, j * 16u, xr[u]);
+          buf_st4(rm, j * 16u, mr[u]);
+          if constexpr (HASV) buf_st4(rv, j * 16u, vr[u]);
+        }
+      } else {                                                   // ragged end of a tensor
+        for (uint32_t j = j0 + tid; j < n4; j += BLOCK) {
+          f32x4 xr = buf_ld4(rx, j * 16u), gr = load_grad4<BF16G>(rg, j), mr = buf_ld4(rm, j * 16u), vr;
+          if constexpr (HASV) vr = buf_ld4(rv, j * 16u);
+          update_vec4<KIND, UNDO>(xr, gr, mr, vr, c);
+          buf_st4(rx, j * 16u, xr);
+          buf_st4(rm, j * 16u, mr);
+          if constexpr (HASV) buf_st4(rv, j * 16u, vr);
+        }
+        const uint32_t e = (n4 << 2) + tid;                      // last numel % 4 elements
+        if (e < len) {                                           // (they start inside this tile)
+          float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
+          if constexpr (HASV) ve = ld<false>(vp + e);
+          update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
+          st<false>(xp + e, xe);
+          st<false>(mp + e, me);
+          if constexpr (HASV) st<false>(vp + e, ve);
         }
       }
-      for (uint32_t j = i + tid; j < n4; j += kThreads) {       // ragged end of the chunk
-        f32x4 xr = ld<NT>(x4 + j), gr = load_grad4<BF16G, NT>(gp, j), mr = ld<NT>(m4 + j), vr;
-        if constexpr (HASV) vr = ld<NT>(v4 + j);
-        update_vec4<KIND, UNDO>(xr, gr, mr, vr, c);
-        st<NT>(x4 + j, xr);
-        st<NT>(m4 + j, mr);
-        if constexpr (HASV) st<NT>(v4 + j, vr);
-      }
-      const uint32_t e = (n4 << 2) + tid;                        // last numel % 4 elements
-      if (e < len) {
-        float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
-        if constexpr (HASV) ve = ld<false>(vp + e);
-        update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
-        st<false>(xp + e, xe);
-        st<false>(mp + e, me);
-        if constexpr (HASV) st<false>(vp + e, ve);
-      }
-    } else {
-      for (uint32_t e = tid; e < len; e += kThreads) {           // unaligned tensor: 4-byte accesses
+    } else {                                                     // unaligned tensor: 4-byte accesses
+      const uint32_t e1 = (e0 + TILE4 * 4u < len) ? e0 + TILE4 * 4u : len;
+      for (uint32_t e = e0 + tid; e < e1; e += BLOCK) {
         float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
         if constexpr (HASV) ve = ld<false>(vp + e);
         update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
@@ -222,22 +268,23 @@ opt_kernel(const TensorDesc *__restrict__ descs, const ChunkRef *__restrict__ ch
   }
 }
 
-// Plain copy with the optimizer kernels' access pattern (16 bytes per lane, grid stride over
-// tiles of U*256 vectors): the practical HBM ceiling and the calibration run for byte counters.
-template <bool NT, int U>
-__global__ void __launch_bounds__(kThreads)
+// Plain copy with the same launch shape (one tile of U*BLOCK 16-byte vectors per workgroup): the
+// practical HBM ceiling of a 1-read/1-write stream and the calibration run for byte counters.
+template <int U, int BLOCK>
+__global__ void __launch_bounds__(BLOCK)
 copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, uint64_t n16) {
-  const uint64_t tile = (uint64_t)U * kThreads;
+  constexpr bool NT = SWIFT_NT != 0;
+  const uint64_t tile = (uint64_t)U * BLOCK;
   const uint64_t n_tiles = (n16 + tile - 1) / tile;
   for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
     const uint64_t i0 = t * tile + threadIdx.x;
     u32x4 r[U];
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      if (i0 + (uint64_t)u * kThreads < n16) r[u] = ld<NT>(src + i0 + (uint64_t)u * kThreads);
+      if (i0 + (uint64_t)u * BLOCK < n16) r[u] = ld<NT>(src + i0 + (uint64_t)u * BLOCK);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      if (i0 + (uint64_t)u * kThreads < n16) st<NT>(dst + i0 + (uint64_t)u * kThreads, r[u]);
+      if (i0 + (uint64_t)u * BLOCK < n16) st<NT>(dst + i0 + (uint64_t)u * BLOCK, r[u]);
   }
 }
 
