@@ -110,6 +110,9 @@ def main() -> int:
     ap.add_argument("--workload", default="llama7b_adamw")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=128 * 1024 * 1024)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="only run swift_stream_copy on BYTES bytes five times (a copy of known size, to "
+                         "scale a profiler's HBM byte counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU: the update-undo path needs no communication, every replica "
@@ -123,6 +126,19 @@ def main() -> int:
         log("bench.py: no GPU visible")
         return 2
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = args.copy_calibration // 16 * 16
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(0x3c)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            B.swift_stream_copy(dst, src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        print(json.dumps({"copy_bytes": n, "launches": 5, "ms_per_launch": 1e3 * dt,
+                          "gb_per_s": 2 * n / dt / 1e9}), flush=True)
+        return 0
     w = synth.workloads()[args.workload]
     N, n_t = w.n_params, len(w.shapes)
     log(f"[bench] workload {w.name}: {n_t} tensors, {N:,} params; drawing state on the GPU ...")
@@ -187,10 +203,6 @@ def main() -> int:
 
     for _ in range(args.warmup):
         one_pass()
-    torch.cuda.synchronize()
-    if dmask.cpu().tolist() != [1 if (b and synth.numel(s)) else 0 for b, s in zip(mask, w.shapes)]:
-        log("[bench] ERROR: digest-derived mask differs from the step mask")
-        return 1
     all_events = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -200,6 +212,9 @@ def main() -> int:
         all_events.append(ev)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if dmask.cpu().tolist() != [1 if (b and synth.numel(s)) else 0 for b, s in zip(mask, w.shapes)]:
+        log("[bench] ERROR: digest-derived mask differs from the step mask")
+        return 1
 
     seg_ms = {s: 0.0 for s in segs}
     for ev in all_events:

@@ -74,16 +74,6 @@ int device_info(int dev, DeviceInfo *out) {
   return SWIFT_OK;
 }
 
-// Resident workgroups per compute unit for `kernel`, from the runtime's occupancy calculator.
-int resident_groups(const void *kernel, int *out) {
-  int nb = 0;
-  SWIFT_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kThreads, 0));
-  long forced = env_long("SWIFT_WG_PER_CU", 0);      // tuning knob for sweeps
-  if (forced > 0 && forced <= 64) nb = (int)forced;
-  *out = nb < 1 ? 1 : nb;
-  return SWIFT_OK;
-}
-
 // ------------------------------------------------------------------------------------------
 // Plans: descriptor table + chunk table in one device allocation, cached by the exact
 // contents of the host arrays that produced them.
@@ -380,7 +370,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   return SWIFT_OK;
 }
 
-typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const uint8_t *, const OptConsts);
+typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, uint32_t, const uint8_t *, const OptConsts);
 
 template <int U, int BLOCK>
 OptKernel pick_kernel_shape(int kind, bool undo, bool bf16) {
@@ -425,11 +415,27 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   if (plan->n_chunks == 0) return SWIFT_OK;
   uint32_t tpc_shift = 0;
   while ((tile_elems << tpc_shift) < plan->chunk_elems) ++tpc_shift;
-  const uint64_t n_work = (uint64_t)plan->n_chunks << tpc_shift;
-  const uint32_t grid = (uint32_t)std::min<uint64_t>(n_work, 0x7fffffffull);
+  // Tiles per workgroup: one, except with a device mask, where skipped tensors still cost a
+  // dispatch per group, so groups are larger (both can be overridden for sweeps).
+  uint32_t grp_shift = (uint32_t)env_long(want_dmask ? "SWIFT_GROUP_SHIFT_DMASK" : "SWIFT_GROUP_SHIFT",
+                                          want_dmask ? SWIFT_DEFAULT_GROUP_SHIFT_DMASK : 0);
+  if (grp_shift > tpc_shift) grp_shift = tpc_shift;
+  const uint64_t n_groups = ((uint64_t)plan->n_chunks << tpc_shift) >> grp_shift;
+  uint64_t grid_cap = 0x7fffffffull;
+  if (want_dmask) {
+    // With a device mask the host cannot size the grid to the marked tensors, and every skipped
+    // tile still costs a dispatch (about 0.9 ns).  A grid capped at about two thirds of a large
+    // list, strided over, measured best for half-marked lists (6.1 against 5.7 TB/s on the 7B
+    // list) and nearly halves the cost of an almost empty mask.  Callers with a sparse mask and
+    // no reason to avoid a host round trip should prefer the host-mask entry points, whose grid
+    // covers the marked tensors only.
+    const long per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
+    if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
+  }
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(n_groups, grid_cap);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3((uint32_t)tune.block), lds_cap_bytes(info, tune),
-                     static_cast<hipStream_t>(stream), static_cast<const ChunkDesc *>(plan->chunks()), n_work,
-                     tpc_shift, device_mask, c);
+                     static_cast<hipStream_t>(stream), static_cast<const ChunkDesc *>(plan->chunks()), n_groups,
+                     tpc_shift, grp_shift, device_mask, c);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }
@@ -454,18 +460,18 @@ int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, b
   return total;
 }
 
-// Digest chunks: as large as still leaves every resident workgroup several chunks.
-uint32_t digest_chunk_elems(uint64_t total, uint64_t resident_wgs) {
-  const uint32_t tile = (uint32_t)SWIFT_UNROLL * kThreads * 4;
+// Digest chunks: one workgroup and one 64-bit atomic per chunk.
+// Whole-buffer shards of large tensors get longer chunks: fewer atomics land on one address.
+uint32_t digest_chunk_elems(uint64_t total, int64_t shard_elems) {
+  const uint32_t tile = 4u * kThreads * 4;                     // largest unroll the kernel is built with
   long forced = env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0);       // tuning knob for sweeps
   if (forced >= (long)tile && forced <= (1l << 22) && forced % tile == 0) return (uint32_t)forced;
-  uint32_t ce = 16384;
-  while (ce > 4096 && total / ce < 8 * resident_wgs) ce >>= 1;
-  return ce < tile ? tile : ce;
+  if (total < (1ull << 26)) return tile;
+  return shard_elems == 0 ? 4u * SWIFT_DIGEST_CHUNK : SWIFT_DIGEST_CHUNK;
 }
 
 int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *numel, int64_t shard_elems, int dev,
-                      uint64_t resident_wgs, std::shared_ptr<Plan> *out) {
+                      std::shared_ptr<Plan> *out) {
   std::string key;
   key.reserve(64 + (size_t)n_buf * 16);
   key_add(key, (uint8_t)'D');
@@ -498,7 +504,7 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   plan->key = std::move(key);
   plan->device = dev;
   plan->n_out = n_out;
-  plan->chunk_elems = digest_chunk_elems(total, resident_wgs);
+  plan->chunk_elems = digest_chunk_elems(total, shard_elems);
   const uint64_t ce = plan->chunk_elems;
   std::vector<ChunkRef> chunks;
   chunks.reserve((size_t)(total / ce) + (size_t)n_out);
@@ -566,12 +572,10 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
   DeviceInfo info;
   if ((rc = device_info(dev, &info))) return rc;
   if ((rc = check_device_range(out_device, (size_t)n_out * 8, dev, "out_device", 0))) return rc;
-  const auto kernel = digest_kernel<SWIFT_NT != 0, SWIFT_UNROLL>;
-  int per_cu = 1;
-  if ((rc = resident_groups(reinterpret_cast<const void *>(kernel), &per_cu))) return rc;
-  const uint64_t resident = (uint64_t)info.cus * (uint64_t)per_cu;
+  const long du = env_long("SWIFT_DIGEST_U", SWIFT_DIGEST_U);   // tuning knob for sweeps
+  const auto kernel = du == 1 ? digest_kernel<1> : du == 2 ? digest_kernel<2> : digest_kernel<4>;
   std::shared_ptr<Plan> plan;
-  if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, resident, &plan))) return rc;
+  if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, &plan))) return rc;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   // The output is cleared by a kernel (not a memset node) so that the call can be captured in a graph.
   const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
@@ -579,7 +583,7 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
                      (uint64_t)0);
   SWIFT_HIP(hipGetLastError());
   if (plan->n_chunks == 0) return SWIFT_OK;
-  const uint32_t grid = (uint32_t)std::min<uint64_t>(plan->n_chunks, resident);
+  const uint32_t grid = plan->n_chunks;                        // one workgroup per chunk
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
                      static_cast<const ChunkRef *>(plan->chunks()), plan->n_chunks, plan->chunk_elems,
                      (uint64_t)shard_elems,

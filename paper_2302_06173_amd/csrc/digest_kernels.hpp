@@ -63,14 +63,16 @@ __global__ void __launch_bounds__(kThreads) fill_u64_kernel(uint64_t *p, uint64_
     p[i] = value;
 }
 
+// One workgroup per chunk (the grid equals the chunk count; the loop only covers a capped grid).
 // Chunk numbering inside a buffer: a full shard spans cps = ceil(S / chunk_elems) chunk numbers,
 // chunk = shard * cps + k covers words [shard*S + k*CE, ...) of the buffer, i.e. shard-relative
 // indices [k*CE, min(k*CE + CE, shard length)).  S = shard_elems, or numel when shard_elems = 0.
 // `out` must be zero when the kernel starts.
-template <bool NT, int U>
+template <int U>
 __global__ void __launch_bounds__(kThreads)
 digest_kernel(const DigestDesc *__restrict__ descs, const ChunkRef *__restrict__ chunks, uint32_t n_chunks,
               uint32_t chunk_elems, uint64_t shard_elems, unsigned long long *__restrict__ out) {
+  constexpr bool NT = SWIFT_NT != 0;
   __shared__ uint64_t wave_part[kThreads / 64];
   const uint32_t tid = threadIdx.x;
   for (uint32_t ci = blockIdx.x; ci < n_chunks; ci += gridDim.x) {

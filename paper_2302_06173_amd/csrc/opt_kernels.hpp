@@ -14,8 +14,9 @@ namespace swift {
 
 constexpr int kSGDM = 0, kADAM = 1, kADAMW = 2;
 constexpr int kThreads = 256;           // 4 wavefronts of 64
-#ifndef SWIFT_UNROLL
-#define SWIFT_UNROLL 2                  // digest kernel: 16-byte loads in flight per lane
+#ifndef SWIFT_DIGEST_U
+#define SWIFT_DIGEST_U 1                // digest kernel: 16-byte loads in flight per lane
+#define SWIFT_DIGEST_CHUNK 65536        // digest kernel: words per workgroup (large inputs)
 #endif
 // Launch shapes of the optimizer kernels that get compiled: X(U, BLOCK).
 #ifndef SWIFT_SHAPES
@@ -26,6 +27,8 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #define SWIFT_DEFAULT_BLOCK 64
 #define SWIFT_DEFAULT_WAVES_PER_CU 11
 #define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
+#define SWIFT_DEFAULT_GROUP_SHIFT_DMASK 0
+#define SWIFT_DEFAULT_DMASK_WGS_PER_CU 16384
 #endif
 #ifndef SWIFT_NT
 #define SWIFT_NT 1                      // non-temporal (streaming) loads and stores
@@ -179,84 +182,53 @@ __device__ __forceinline__ float load_grad1(const void *g, int64_t i) {
   else return ld<false>(reinterpret_cast<const float *>(g) + i);
 }
 
-// One workgroup per tile.  A tile is U*BLOCK 16-byte vectors (U*BLOCK*4 elements) of one chunk; a
-// chunk is up to `chunk_elems` consecutive elements of one tensor (the last chunk of a tensor is
-// short) and spans tiles_per_chunk = 1 << tpc_shift work items, so work item w is tile
-// (w & (tpc-1)) of chunk (w >> tpc_shift).  The chunk table holds ready-made pointers, so a
-// wavefront is one scalar load away from issuing its vector loads.  The grid normally equals the
-// number of work items: the hardware dispatcher then hands tiles out in address order as
-// wavefronts retire, which keeps the window of HBM pages in flight narrow (a persistent
-// grid-stride loop lets workgroups drift apart and measured 10-20 % slower for this
-// 4-read/3-write pattern).  The launch passes dynamic LDS that is never touched: it only caps how
-// many workgroups share a compute unit, because more than ~10 wavefronts per CU in flight lowers
-// the achieved HBM bandwidth of the mixed read/write stream.
-// `dmask` (nullable) holds one byte per tensor in device memory: tiles of tensors whose byte is
-// zero are skipped.
+// One tile: U*BLOCK 16-byte vectors (U*BLOCK*4 elements) of one chunk, starting at element
+// ti * U*BLOCK*4 of the chunk (the caller has checked that this is inside the chunk).
 template <int KIND, bool UNDO, bool BF16G, int U, int BLOCK>
-__global__ void __launch_bounds__(BLOCK)
-opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_work, uint32_t tpc_shift,
-           const uint8_t *__restrict__ dmask, const OptConsts c) {
+__device__ __forceinline__ void process_tile(const ChunkDesc &d, uint32_t ti, uint32_t tid, const OptConsts &c) {
   constexpr bool HASV = (KIND != kSGDM);
   constexpr uint32_t TILE4 = U * BLOCK;                          // vectors per tile
-  const uint32_t tid = threadIdx.x;
-  for (uint64_t w = blockIdx.x; w < n_work; w += gridDim.x) {
-    const ChunkDesc d = chunks[w >> tpc_shift];
-    const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
-    const uint32_t len = d.len;
-    const uint32_t e0 = ti * (TILE4 * 4u);                       // first element of this tile in the chunk
-    if (e0 >= len) continue;                                     // short last chunk: nothing here
-    if (dmask != nullptr && dmask[d.tensor] == 0) continue;
-    float *__restrict__ xp = d.x;
-    float *__restrict__ mp = d.m;
-    float *__restrict__ vp = d.v;
-    const void *gp = d.g;
-    if (d.vec_ok) {
-      // chunk starts are multiples of 4 elements, so chunks keep their tensor's 16-byte alignment
-      const uint32_t n4 = len >> 2;
-      const __amdgpu_buffer_rsrc_t rx = make_rsrc(xp, n4 * 16u), rm = make_rsrc(mp, n4 * 16u);
-      const __amdgpu_buffer_rsrc_t rv = make_rsrc(vp, HASV ? n4 * 16u : 0u);
-      const __amdgpu_buffer_rsrc_t rg = make_rsrc(gp, n4 * (BF16G ? 8u : 16u));
-      const uint32_t j0 = ti * TILE4;
-      if (j0 + TILE4 <= n4) {                                    // full tile: no predicates
-        f32x4 xr[U], gr[U], mr[U], vr[U];
+  const uint32_t len = d.len;
+  float *__restrict__ xp = d.x;
+  float *__restrict__ mp = d.m;
+  float *__restrict__ vp = d.v;
+  const void *gp = d.g;
+  if (d.vec_ok) {
+    // chunk starts are multiples of 4 elements, so chunks keep their tensor's 16-byte alignment
+    const uint32_t n4 = len >> 2;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(xp, n4 * 16u), rm = make_rsrc(mp, n4 * 16u);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(vp, HASV ? n4 * 16u : 0u);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc(gp, n4 * (BF16G ? 8u : 16u));
+    const uint32_t j0 = ti * TILE4;
+    if (j0 + TILE4 <= n4) {                                      // full tile: no predicates
+      f32x4 xr[U], gr[U], mr[U], vr[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const uint32_t j = j0 + u * BLOCK + tid;
-          xr[u] = buf_ld4(rx, j * 16u);
-          gr[u] = load_grad4<BF16G>(rg, j);
-          mr[u] = buf_ld4(rm, j * 16u);
-          if constexpr (HASV) vr[u] = buf_ld4(rv, j * 16u);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const uint32_t j = j0 + u * BLOCK + tid;
-          update_vec4<KIND, UNDO>(xr[u], gr[u], mr[u], vr[u], c);
-          buf_st4(rx, j * 16u, xr[u]);
-          buf_st4(rm, j * 16u, mr[u]);
-          if constexpr (HASV) buf_st4(rv, j * 16u, vr[u]);
-        }
-      } else {                                                   // ragged end of a tensor
-        for (uint32_t j = j0 + tid; j < n4; j += BLOCK) {
-          f32x4 xr = buf_ld4(rx, j * 16u), gr = load_grad4<BF16G>(rg, j), mr = buf_ld4(rm, j * 16u), vr;
-          if constexpr (HASV) vr = buf_ld4(rv, j * 16u);
-          update_vec4<KIND, UNDO>(xr, gr, mr, vr, c);
-          buf_st4(rx, j * 16u, xr);
-          buf_st4(rm, j * 16u, mr);
-          if constexpr (HASV) buf_st4(rv, j * 16u, vr);
-        }
-        const uint32_t e = (n4 << 2) + tid;                      // last numel % 4 elements
-        if (e < len) {                                           // (they start inside this tile)
-          float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
-          if constexpr (HASV) ve = ld<false>(vp + e);
-          update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
-          st<false>(xp + e, xe);
-          st<false>(mp + e, me);
-          if constexpr (HASV) st<false>(vp + e, ve);
-        }
+      for (int u = 0; u < U; ++u) {
+        const uint32_t j = j0 + u * BLOCK + tid;
+        xr[u] = buf_ld4(rx, j * 16u);
+        gr[u] = load_grad4<BF16G>(rg, j);
+        mr[u] = buf_ld4(rm, j * 16u);
+        if constexpr (HASV) vr[u] = buf_ld4(rv, j * 16u);
       }
-    } else {                                                     // unaligned tensor: 4-byte accesses
-      const uint32_t e1 = (e0 + TILE4 * 4u < len) ? e0 + TILE4 * 4u : len;
-      for (uint32_t e = e0 + tid; e < e1; e += BLOCK) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t j = j0 + u * BLOCK + tid;
+        update_vec4<KIND, UNDO>(xr[u], gr[u], mr[u], vr[u], c);
+        buf_st4(rx, j * 16u, xr[u]);
+        buf_st4(rm, j * 16u, mr[u]);
+        if constexpr (HASV) buf_st4(rv, j * 16u, vr[u]);
+      }
+    } else {                                                     // ragged end of a tensor
+      for (uint32_t j = j0 + tid; j < n4; j += BLOCK) {
+        f32x4 xr = buf_ld4(rx, j * 16u), gr = load_grad4<BF16G>(rg, j), mr = buf_ld4(rm, j * 16u), vr;
+        if constexpr (HASV) vr = buf_ld4(rv, j * 16u);
+        update_vec4<KIND, UNDO>(xr, gr, mr, vr, c);
+        buf_st4(rx, j * 16u, xr);
+        buf_st4(rm, j * 16u, mr);
+        if constexpr (HASV) buf_st4(rv, j * 16u, vr);
+      }
+      const uint32_t e = (n4 << 2) + tid;                        // last numel % 4 elements
+      if (e < len) {                                             // (they start inside this tile)
         float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
         if constexpr (HASV) ve = ld<false>(vp + e);
         update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
@@ -264,6 +236,59 @@ opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_work, uint32_t tpc_s
         st<false>(mp + e, me);
         if constexpr (HASV) st<false>(vp + e, ve);
       }
+    }
+  } else {                                                       // unaligned tensor: 4-byte accesses
+    const uint32_t e0 = ti * (TILE4 * 4u);
+    const uint32_t e1 = (e0 + TILE4 * 4u < len) ? e0 + TILE4 * 4u : len;
+    for (uint32_t e = e0 + tid; e < e1; e += BLOCK) {
+      float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
+      if constexpr (HASV) ve = ld<false>(vp + e);
+      update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
+      st<false>(xp + e, xe);
+      st<false>(mp + e, me);
+      if constexpr (HASV) st<false>(vp + e, ve);
+    }
+  }
+}
+
+// One workgroup per group of 2^grp_shift consecutive tiles (normally one tile).  A chunk is up to
+// chunk_elems consecutive elements of one tensor (the last chunk of a tensor is short) and spans
+// 2^tpc_shift tile slots, so tile slot w is tile (w & (tpc-1)) of chunk (w >> tpc_shift); groups
+// never straddle chunks (grp_shift <= tpc_shift).  The chunk table holds ready-made pointers, so
+// a wavefront is one scalar load away from issuing its vector loads.  The grid normally equals
+// the number of groups: the hardware dispatcher then hands tiles out in address order as
+// wavefronts retire, which keeps the window of HBM pages in flight narrow (a persistent
+// grid-stride loop lets workgroups drift apart and measured 10-20 % slower for this
+// 4-read/3-write pattern).  The launch passes dynamic LDS that is never touched: it only caps how
+// many workgroups share a compute unit, because more than ~11 wavefronts per CU in flight lowers
+// the achieved HBM bandwidth of the mixed read/write stream.
+// `dmask` (nullable) holds one byte per tensor in device memory: groups of tensors whose byte
+// is zero are skipped (such launches use larger groups, so that skipping costs fewer dispatches).
+template <int KIND, bool UNDO, bool BF16G, int U, int BLOCK>
+__global__ void __launch_bounds__(BLOCK)
+opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_groups, uint32_t tpc_shift, uint32_t grp_shift,
+           const uint8_t *__restrict__ dmask, const OptConsts c) {
+  constexpr uint32_t TILE = U * BLOCK * 4u;                      // elements per tile
+  const uint32_t tid = threadIdx.x;
+  for (uint64_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+    const uint64_t w0 = grp << grp_shift;                        // first tile slot of the group
+    const ChunkDesc d = chunks[w0 >> tpc_shift];
+    const uint32_t ti0 = (uint32_t)w0 & ((1u << tpc_shift) - 1u);
+    if (ti0 * TILE >= d.len) continue;                           // short last chunk: nothing here
+    if (dmask != nullptr) {
+      // the mask byte through the scalar cache: read the aligned 32-bit word that holds it (the
+      // word lies in the same page as the byte, so this never leaves the caller's mapping; the
+      // mask is not written while this kernel runs, which is what the constant space requires)
+      const uintptr_t a = (uintptr_t)(dmask + d.tensor);
+      typedef const __attribute__((address_space(4))) uint32_t *const_u32_ptr;   // constant space: s_load
+      const uint32_t word = *(const_u32_ptr)(a & ~(uintptr_t)3);
+      if (((word >> (8u * (uint32_t)(a & 3u))) & 0xFFu) == 0) continue;
+    }
+    const uint32_t n_tiles = 1u << grp_shift;
+    for (uint32_t k = 0; k < n_tiles; ++k) {
+      const uint32_t ti = ti0 + k;
+      if (ti * TILE >= d.len) break;
+      process_tile<KIND, UNDO, BF16G, U, BLOCK>(d, ti, tid, c);
     }
   }
 }
