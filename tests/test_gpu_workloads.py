@@ -1,0 +1,211 @@
+"""GPU parity at the benchmark's real shapes: the five synthetic workloads, launched exactly as
+bench.py launches them (same binding calls, default launch shape).
+
+Small workloads are compared with the fp64 oracle element by element over every tensor.  For the
+1.5 B and 7 B lists the oracle checks whole sampled tensors plus windows of the largest ones
+(starts, chunk boundaries, ragged ends), and properties that hold at any size cover the rest:
+gradients and unmarked tensors keep their digests (i.e. their bits), every marked non-empty tensor
+changes its digest, and the mask derived from digests on the device equals the step mask."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_parity, binding_hparams, digests_np, oracle_hyper, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2302_06173_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2302_06173_amd import synth
+    return synth
+
+
+def _scale(*arrs):
+    s = 0.0
+    for a in arrs:
+        if a is not None and a.size:
+            s = max(s, float(np.abs(oracle.widen(a)).max()))
+    return s
+
+
+def _check_slices(kind, hpd, pre, post, undo, what):
+    """pre/post: dicts key -> (x, g, m, v) numpy slices taken around one GPU call."""
+    h = oracle_hyper(kind, hpd)
+    fn = oracle.opt_undo if undo else oracle.opt_step
+    for key in pre:
+        x, g, m, v = pre[key]
+        qx, qg, qm, qv = post[key]
+        assert np.array_equal(g.view(np.uint8), qg.view(np.uint8)), f"{what} {key}: gradient written"
+        rx, rm, rv = fn(h, x, g, m, v)
+        sc = _scale(x, g, m, v)
+        assert_parity(qx, rx, f"{what} theta {key}", sc)
+        assert_parity(qm, rm, f"{what} m {key}", sc)
+        if v is not None:
+            assert_parity(qv, rv, f"{what} v {key}", sc * max(sc, 1.0))
+
+
+def _grab(state, picks):
+    """Host copies of the picked (tensor, lo, hi) ranges of all four streams."""
+    out = {}
+    for (i, lo, hi) in picks:
+        v = None if state.v is None else to_np(state.v[i][lo:hi])
+        out[(i, lo, hi)] = (to_np(state.theta[i][lo:hi]), to_np(state.grad[i][lo:hi]), to_np(state.m[i][lo:hi]), v)
+    return out
+
+
+def _all_ranges(shapes, synth):
+    return [(i, 0, synth.numel(s)) for i, s in enumerate(shapes)]
+
+
+def _sample_ranges(shapes, synth, every, window=70001, whole_limit=5_000_000):
+    """Whole tensors for a spread of indices; windows (start, a 65,536-element chunk boundary in the
+    middle, the ragged end) of tensors too large to check whole."""
+    n_t = len(shapes)
+    chosen = sorted(set([0, 1, 2, n_t - 2, n_t - 1] + list(range(3, n_t, every))))
+    picks = []
+    for i in chosen:
+        n = synth.numel(shapes[i])
+        if n <= whole_limit:
+            picks.append((i, 0, n))
+        else:
+            mid = (n // 2) // 65536 * 65536
+            picks += [(i, 0, window), (i, mid - window // 2, mid + window // 2), (i, n - window, n)]
+    return picks
+
+
+# ------------------------------------------------------------------------------------------
+def test_sgdm_flat_1m(B, synth):
+    """Configuration 1: step, undo, comparison with the originals, one digest per 64 Ki-element shard."""
+    w = synth.workloads()["sgdm_flat_1m"]
+    s = synth.make_state(w, "cuda")
+    tl = B.TensorList(s.theta, s.grad, s.m, None)
+    hp = binding_hparams(B, w.kind, w.hyper)
+    picks = _all_ranges(w.shapes, synth)
+    bufs = B.BufferList([s.theta[0], s.m[0]])
+    orig = _grab(s, picks)
+    d0 = B.swift_state_digest(bufs, w.digest_shard)
+    B.swift_opt_step(tl, hp)
+    d1 = B.swift_state_digest(bufs, w.digest_shard)
+    torch.cuda.synchronize()
+    mid = _grab(s, picks)
+    B.swift_opt_undo(tl, hp)
+    d2 = B.swift_state_digest(bufs, w.digest_shard)
+    torch.cuda.synchronize()
+    end = _grab(s, picks)
+    _check_slices(w.kind, w.hyper, orig, mid, False, "sgdm step")
+    _check_slices(w.kind, w.hyper, mid, end, True, "sgdm undo")
+    key = picks[0]
+    for k in (0, 2):                                   # theta and m come back within the stated bar
+        a, b = end[key][k].astype(np.float64), orig[key][k].astype(np.float64)
+        assert (np.abs(a - b) <= np.maximum(1e-5 * np.abs(b), 1e-8)).all()
+    assert d0.numel() == 32
+    assert np.array_equal(digests_np(d0), oracle.digest_list([orig[key][0], orig[key][2]], w.digest_shard))
+    assert np.array_equal(digests_np(d1), oracle.digest_list([mid[key][0], mid[key][2]], w.digest_shard))
+    assert np.array_equal(digests_np(d2), oracle.digest_list([end[key][0], end[key][2]], w.digest_shard))
+    assert (digests_np(d0) != digests_np(d1)).all()    # every shard saw the step
+
+
+@pytest.mark.parametrize("name", ["resnet50_adam", "bert_large_adamw"])
+def test_full_list_elementwise(B, synth, name):
+    """Configurations 2 and 3: every element of every tensor against the oracle, step then undo;
+    configuration 3 also checks the per-tensor digests of theta, m and v."""
+    w = synth.workloads()[name]
+    s = synth.make_state(w, "cuda")
+    tl = B.TensorList(s.theta, s.grad, s.m, s.v)
+    hp = binding_hparams(B, w.kind, w.hyper)
+    picks = _all_ranges(w.shapes, synth)
+    orig = _grab(s, picks)
+    B.swift_opt_step(tl, hp)
+    torch.cuda.synchronize()
+    mid = _grab(s, picks)
+    _check_slices(w.kind, w.hyper, orig, mid, False, f"{name} step")
+    del orig
+    if name == "bert_large_adamw":
+        d = B.swift_state_digest(s.theta + s.m + s.v, 0)
+        torch.cuda.synchronize()
+        want = oracle.digest_list([mid[k][0] for k in picks] + [mid[k][2] for k in picks] + [mid[k][3] for k in picks], 0)
+        assert np.array_equal(digests_np(d), want)
+    B.swift_opt_undo(tl, hp)
+    torch.cuda.synchronize()
+    end = _grab(s, picks)
+    _check_slices(w.kind, w.hyper, mid, end, True, f"{name} undo")
+
+
+def _selective_flow(B, synth, w, every):
+    n_t = len(w.shapes)
+    s = synth.make_state(w, "cuda")
+    tl = B.TensorList(s.theta, s.grad, s.m, s.v)
+    hp = binding_hparams(B, w.kind, w.hyper, w.grad_bf16)
+    frac = w.masked_fraction or 0.5
+    mask = synth.tensor_mask(synth.Workload(**{**w.__dict__, "masked_fraction": frac}), n_t)
+    picks = _sample_ranges(w.shapes, synth, every)
+    on = [p for p in picks if mask[p[0]]]
+    off = [p for p in picks if not mask[p[0]]]
+    assert on and off
+    # gradients are digested too (as 32-bit words; bf16 tensors have an even element count here)
+    gwords = [g.view(torch.int32) if g.dtype == torch.bfloat16 else g for g in s.grad]
+    bufs = B.BufferList(s.theta + s.m + s.v + gwords)
+    orig = _grab(s, picks)
+    d0 = B.swift_state_digest(bufs, 0)
+    B.swift_opt_step(tl, hp, host_mask=mask)                       # the interrupted update
+    d1 = B.swift_state_digest(bufs, 0)
+    dmask = B.swift_mask_from_digests(d0[:3 * n_t], d1[:3 * n_t], n_t)
+    torch.cuda.synchronize()
+    mid = _grab(s, picks)
+    a, b = digests_np(d0).reshape(4, n_t), digests_np(d1).reshape(4, n_t)
+    assert np.array_equal(a[3], b[3]), "a gradient changed"
+    changed = (a[:3] != b[:3])
+    assert np.array_equal(changed.all(axis=0), np.array(mask, bool)), "theta, m and v of exactly the marked tensors change"
+    assert np.array_equal(dmask.cpu().numpy(), np.array(mask, np.uint8))
+    # the oracle's hash of the sampled whole tensors agrees with the device digests
+    for (i, lo, hi) in picks:
+        if lo == 0 and hi == synth.numel(w.shapes[i]):
+            assert a[0][i] == oracle.digest(orig[(i, lo, hi)][0])[0]
+            assert b[1][i] == oracle.digest(mid[(i, lo, hi)][2])[0]
+    _check_slices(w.kind, w.hyper, {k: orig[k] for k in on}, {k: mid[k] for k in on}, False, f"{w.name} masked step")
+    for k in off:
+        for j in (0, 2, 3):
+            assert np.array_equal(orig[k][j].view(np.uint32), mid[k][j].view(np.uint32)), f"unmarked {k} changed"
+    del orig
+    B.swift_opt_undo_dmask(tl, hp, dmask)                          # selective undo, mask stays on the device
+    d2 = B.swift_state_digest(bufs, 0)
+    torch.cuda.synchronize()
+    end = _grab(s, picks)
+    c = digests_np(d2).reshape(4, n_t)
+    assert np.array_equal(c[3], a[3])
+    off_idx = ~np.array(mask, bool)
+    assert np.array_equal(c[:3, off_idx], a[:3, off_idx]), "an unmarked tensor changed during undo"
+    _check_slices(w.kind, w.hyper, {k: mid[k] for k in on}, {k: end[k] for k in on}, True, f"{w.name} selective undo")
+    for k in off:
+        for j in (0, 2, 3):
+            assert np.array_equal(mid[k][j].view(np.uint32), end[k][j].view(np.uint32))
+    # and one full-list step + undo in the launch configuration the benchmark times
+    B.swift_opt_step(tl, hp)
+    torch.cuda.synchronize()
+    full = _grab(s, picks)
+    _check_slices(w.kind, w.hyper, end, full, False, f"{w.name} full step")
+    B.swift_opt_undo(tl, hp)
+    torch.cuda.synchronize()
+    _check_slices(w.kind, w.hyper, full, _grab(s, picks), True, f"{w.name} full undo")
+
+
+def test_gpt2_xl_bf16_gradients_sampled(B, synth):
+    """Configuration 4 (1.56 B parameters, bf16 gradients widened in the kernel)."""
+    _selective_flow(B, synth, synth.workloads()["gpt2_xl_adamw_bf16g"], every=97)
+
+
+def test_llama7b_selective_undo_sampled(B, synth):
+    """Configuration 5 (6.74 B parameters, 107.8 GB of state, zeros and outliers in g)."""
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 125e9:
+        pytest.skip("needs about 110 GB of free device memory")
+    _selective_flow(B, synth, synth.workloads()["llama7b_adamw"], every=41)
