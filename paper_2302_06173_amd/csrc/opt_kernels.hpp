@@ -270,11 +270,16 @@ opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_groups, uint32_t tpc
            const uint8_t *__restrict__ dmask, const OptConsts c) {
   constexpr uint32_t TILE = U * BLOCK * 4u;                      // elements per tile
   const uint32_t tid = threadIdx.x;
-  for (uint64_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+  // The host launches at most n_groups workgroups, so the first pass needs no bounds test (and no
+  // wait for n_groups before the chunk entry can be fetched).
+  uint64_t grp = blockIdx.x;
+  do {
     const uint64_t w0 = grp << grp_shift;                        // first tile slot of the group
     const ChunkDesc d = chunks[w0 >> tpc_shift];
     const uint32_t ti0 = (uint32_t)w0 & ((1u << tpc_shift) - 1u);
-    if (ti0 * TILE >= d.len) continue;                           // short last chunk: nothing here
+    // (the pointer test is always true for a chunk with elements; it makes the compiler fetch the
+    //  whole entry with one round of scalar loads instead of the length first and the pointers later)
+    if (ti0 * TILE >= d.len || d.x == nullptr) continue;         // short last chunk: nothing here
     if (dmask != nullptr) {
       // the mask byte through the scalar cache: read the aligned 32-bit word that holds it (the
       // word lies in the same page as the byte, so this never leaves the caller's mapping; the
@@ -290,7 +295,7 @@ opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_groups, uint32_t tpc
       if (ti * TILE >= d.len) break;
       process_tile<KIND, UNDO, BF16G, U, BLOCK>(d, ti, tid, c);
     }
-  }
+  } while ((grp += gridDim.x) < n_groups);
 }
 
 // Plain copy with the same launch shape (one tile of U*BLOCK 16-byte vectors per workgroup): the
