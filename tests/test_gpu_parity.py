@@ -117,6 +117,30 @@ def test_step_then_undo_match_oracle_elementwise(B, synth, kind, bf16):
             assert (np.abs(a - b) <= np.maximum(1e-5 * np.abs(b), 1e-8)).all(), (kind, i, k)
 
 
+@pytest.mark.parametrize("bf16", [False, True], ids=["g_f32", "g_bf16"])
+@pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
+def test_undo_from_a_state_the_oracle_stepped(B, synth, kind, bf16):
+    # the undo's inputs owe nothing to the GPU: the oracle steps the seeded state in fp64, its result
+    # rounded to fp32 is what a replica would hold, and both sides undo those same bits
+    s = make(synth, kind, SHAPES, seed=17, bf16=bf16)
+    orig = snapshot(s)
+    h = oracle_hyper(kind, HP[kind])
+    stepped = [[], orig[1], [], None if orig[3] is None else []]
+    for i in range(len(orig[0])):
+        rx, rm, rv = oracle.opt_step(h, orig[0][i], orig[1][i], orig[2][i], None if orig[3] is None else orig[3][i])
+        stepped[0].append(rx.astype(np.float32))
+        stepped[2].append(rm.astype(np.float32))
+        if rv is not None:
+            stepped[3].append(rv.astype(np.float32))
+        s.theta[i].copy_(torch.from_numpy(stepped[0][-1]))
+        s.m[i].copy_(torch.from_numpy(stepped[2][-1]))
+        if rv is not None:
+            s.v[i].copy_(torch.from_numpy(stepped[3][-1]))
+    B.swift_opt_undo(tensor_list(B, s), binding_hparams(B, kind, HP[kind], bf16))
+    torch.cuda.synchronize()
+    check_against_oracle(kind, HP[kind], tuple(stepped), snapshot(s), None, True, f"{kind} undo of an oracle step")
+
+
 @pytest.mark.parametrize("kind", ["sgdm", "adam", "adamw"])
 def test_alignment_does_not_change_result_bits(B, synth, kind):
     # the same values at 16-byte-aligned addresses and at addresses 4 (or 2, bf16) bytes past one

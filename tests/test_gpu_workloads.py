@@ -209,3 +209,69 @@ def test_llama7b_selective_undo_sampled(B, synth):
     if free < 125e9:
         pytest.skip("needs about 110 GB of free device memory")
     _selective_flow(B, synth, synth.workloads()["llama7b_adamw"], every=41)
+
+
+def test_tensor_beyond_2_pow_32_elements(B, synth):
+    """Maximum sizes: one SGDM tensor of 2^32 + 70,003 elements (element offsets need 64 bits) checked
+    on windows at the start, across the 2^32 boundary and at the ragged end; and a digest of a buffer of
+    2^32 - 4 words in one shard (the largest index that fits the 32-bit index field) against the CPU hash."""
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60e9:
+        pytest.skip("needs about 55 GB of free device memory")
+    n = (1 << 32) + 70003
+    hpd = dict(lr=0.1, momentum=0.9, dampening=0.0, weight_decay=1e-4, step=1)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(99)
+    x = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 0.02, generator=gen)
+    g = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gen)
+    m = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gen)
+    s = synth.State([x], [g], [m], None)
+    b = 1 << 32
+    picks = [(0, 0, 70001), (0, b - 35000, b + 35001), (0, n - 70001, n)]
+    tl = B.TensorList(s.theta, s.grad, s.m, None)
+    hp = binding_hparams(B, "sgdm", hpd)
+    pre = _grab(s, picks)
+    B.swift_opt_step(tl, hp)
+    torch.cuda.synchronize()
+    mid = _grab(s, picks)
+    _check_slices("sgdm", hpd, pre, mid, False, "huge step")
+    B.swift_opt_undo(tl, hp)
+    torch.cuda.synchronize()
+    _check_slices("sgdm", hpd, mid, _grab(s, picks), True, "huge undo")
+    # digest: whole-buffer shard at the index limit, and fixed shards over the 2^32 boundary
+    words = x[: b - 4]
+    d = B.swift_state_digest([words], 0)
+    torch.cuda.synchronize()
+    host = to_np(words)
+    assert digests_np(d)[0] == oracle.digest(host)[0]
+    del host
+    with pytest.raises(B.SwiftError):
+        B.swift_state_digest([x], 0)                       # 2^32 words or more need shard_elems
+    shard = (1 << 31) + 12345
+    d = B.swift_state_digest([x], shard)
+    torch.cuda.synchronize()
+    assert d.numel() == 3
+    tail = to_np(x[2 * shard:])
+    assert digests_np(d)[2] == oracle.digest(tail)[0]
+
+
+def test_ten_thousand_tiny_tensors(B, synth):
+    """Many small tensors in one launch: sizes 1..37 elements cycling, every element checked."""
+    shapes = [((i % 37) + 1,) for i in range(10000)]
+    hpd = dict(lr=1e-3, weight_decay=0.01, beta1=0.9, beta2=0.999, eps=1e-8, step=3)
+    w = synth.Workload("tiny", shapes, "adam", hpd, seed=123, zero_frac=0.1, outlier_frac=0.01)
+    s = synth.make_state(w, "cuda")
+    # one flat copy per stream makes the host snapshots cheap; the tensors stay separate allocations
+    tl = B.TensorList(s.theta, s.grad, s.m, s.v)
+    hp = binding_hparams(B, "adam", hpd)
+    flat = lambda ts: torch.cat(ts).cpu().numpy()
+    pre = (flat(s.theta), flat(s.grad), flat(s.m), flat(s.v))
+    B.swift_opt_step(tl, hp)
+    torch.cuda.synchronize()
+    mid = (flat(s.theta), flat(s.grad), flat(s.m), flat(s.v))
+    _check_slices("adam", hpd, {"all": pre}, {"all": mid}, False, "tiny step")
+    B.swift_opt_undo(tl, hp)
+    torch.cuda.synchronize()
+    end = (flat(s.theta), flat(s.grad), flat(s.m), flat(s.v))
+    _check_slices("adam", hpd, {"all": mid}, {"all": end}, True, "tiny undo")
