@@ -57,21 +57,27 @@ def measured_traffic(workload: str):
 
 
 def cpu_baseline(w, state, hp_dict, sample_elems: int):
-    """The oracle, as it stands, on the first `sample_elems` elements of the first tensor: AdamW
-    step then undo (its own fp64 state) plus the digest of theta, m and v; all cores, static split."""
+    """The oracle, as it stands, on the first `sample_elems` elements of the list: AdamW step then
+    undo (its own fp64 state) plus the digest of theta, m and v; all cores, static split."""
     import concurrent.futures as cf
     import numpy as np
     import oracle
 
-    n = min(sample_elems, state.theta[0].numel())
-    cores = min(len(os.sched_getaffinity(0)), 16)
     import torch
 
-    def host(t):
-        t = t[:n]
-        return (t if t.dtype == torch.float32 else t.float()).cpu().numpy()    # bf16 -> fp32 is exact
+    def head(ts):
+        """The first sample_elems elements of the list, tensors concatenated in list order."""
+        parts, left = [], sample_elems
+        for t in ts:
+            if left <= 0:
+                break
+            parts.append(t[:left] if t.dtype == torch.float32 else t[:left].float())   # bf16 -> fp32 is exact
+            left -= parts[-1].numel()
+        return torch.cat(parts).cpu().numpy()
 
-    x32, g32, m32, v32 = host(state.theta[0]), host(state.grad[0]), host(state.m[0]), host(state.v[0])
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    x32, g32, m32, v32 = head(state.theta), head(state.grad), head(state.m), head(state.v)
+    n = x32.size
     x, g, m, v = (oracle.widen(a) for a in (x32, g32, m32, v32))
     oh = oracle.Hyper("adamw", eta=hp_dict["lr"], lam=hp_dict["weight_decay"], beta1=hp_dict["beta1"],
                       beta2=hp_dict["beta2"], eps=hp_dict["eps"], t=hp_dict["step"])
@@ -97,7 +103,7 @@ def cpu_baseline(w, state, hp_dict, sample_elems: int):
     oracle.opt_undo(oh, sx, g[:n1], sm, sv)
     t1 = time.perf_counter() - t0
     return {"value": 2 * n / best, "unit": "params/s", "cores": cores, "kind": "oracle",
-            "sample": f"AdamW step+undo and 3 digests on the first {n} elements of tensor 0 of {w.name}, "
+            "sample": f"AdamW step+undo and 3 digests on the first {n} elements of the {w.name} list, "
                       f"static split over {cores} threads, best of 3",
             "single_thread_value": 2 * n1 / t1}
 

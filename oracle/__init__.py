@@ -5,15 +5,19 @@ leg of ``bench.py`` may import this package; the GPU library and its Python bind
 never do, and this package imports nothing from them.
 
 The arithmetic lives in ``swift_oracle.c`` (plain scalar binary64 loops, one function
-per algorithm of the paper: Alg. 1, Alg. 2 and the six algorithms of App. A).  This
-module only compiles that file with gcc, widens inputs to fp64 and walks tensor lists.
+per algorithm of the paper: Alg. 1, Alg. 2 and the six algorithms of App. A; plus LAMB
+with the saved-norm undo that the paper's "Update-undo" section sketches in one sentence).
+This module only compiles that file with gcc, widens inputs to fp64 and walks tensor lists.
 
 Pins (see ``tests/test_oracle_pins.py``): hand-worked exact-rational examples stored
 under ``tests/golden/``, torch.optim's SGD / Adam / AdamW in fp64 (an independent
 library routine the step reduces to), closed forms, and brute-force exact-rational
 round trips.  The digest has no definition in the paper; it is pinned to stored test
 vectors, to an explicit inverse of its mixer and to order / shard invariants, and is
-"parity unpinned" with respect to the paper itself.
+"parity unpinned" with respect to the paper itself.  LAMB: the paper prints no algorithm, so
+the step follows the LAMB publication and is "parity unpinned" with respect to the paper; it
+is pinned to the AdamW oracle (LAMB = AdamW with the trust ratio folded into the learning
+rate), to hand-worked examples, to its zero-norm fallback and to scaling laws.
 """
 from __future__ import annotations
 
@@ -30,7 +34,7 @@ _SRC = os.path.join(_HERE, "swift_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
-SGDM, ADAM, ADAMW = "sgdm", "adam", "adamw"
+SGDM, ADAM, ADAMW, LAMB = "sgdm", "adam", "adamw", "lamb"
 
 
 def build(force: bool = False) -> str:
@@ -56,6 +60,9 @@ def _load():
             getattr(lib, "oracle_" + name).argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p]
         for name in ("sgdm_step", "sgdm_undo", "adam_step", "adam_undo", "adamw_step", "adamw_undo"):
             getattr(lib, "oracle_" + name).restype = None
+        lib.oracle_lamb_step.argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p, p]
+        lib.oracle_lamb_undo.argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p, p]
+        lib.oracle_lamb_step.restype = lib.oracle_lamb_undo.restype = None
         lib.oracle_digest.argtypes = [p, i64]
         lib.oracle_digest.restype = ctypes.c_uint64
         _lib = lib
@@ -133,6 +140,36 @@ def opt_undo(hp: Hyper, x_new, g, m_new, v_new=None):
     if hp.kind == ADAMW and 1.0 - hp.eta * hp.lam == 0.0:
         raise ZeroDivisionError("undo: eta*lambda = 1 is not invertible")
     return _run("undo", hp, x_new, g, m_new, v_new)
+
+
+def lamb_step(hp: Hyper, x, g, m, v):
+    """LAMB step of ONE tensor: returns (x_{t+1}, m_t, v_t, norms) with norms = [||x_t||, ||u||], the two
+    scalars the undo needs (the paper's saved L2 norm)."""
+    lib = _load()
+    x, g, m, v = widen(x), widen(g), widen(m), widen(v)
+    n = x.size
+    if not (g.size == m.size == v.size == n):
+        raise ValueError("oracle: x, g, m, v differ in size")
+    xo, mo, vo, norms = np.empty(n), np.empty(n), np.empty(n), np.zeros(2)
+    lib.oracle_lamb_step(n, _ptr(x), _ptr(g), _ptr(m), _ptr(v), hp.eta, hp.lam, hp.beta1, hp.beta2, hp.eps,
+                         int(hp.t), _ptr(xo), _ptr(mo), _ptr(vo), _ptr(norms))
+    return xo, mo, vo, norms
+
+
+def lamb_undo(hp: Hyper, x_new, g, m_new, v_new, norms):
+    """Undo of lamb_step for ONE tensor, given the norms that step returned."""
+    if hp.beta1 == 0.0 or hp.beta2 == 0.0:
+        raise ZeroDivisionError("undo: beta = 0 is not invertible")
+    lib = _load()
+    x, g, m, v = widen(x_new), widen(g), widen(m_new), widen(v_new)
+    norms = np.ascontiguousarray(norms, dtype=np.float64)
+    n = x.size
+    if not (g.size == m.size == v.size == n) or norms.size != 2:
+        raise ValueError("oracle: sizes differ")
+    xo, mo, vo = np.empty(n), np.empty(n), np.empty(n)
+    lib.oracle_lamb_undo(n, _ptr(x), _ptr(g), _ptr(m), _ptr(v), hp.eta, hp.lam, hp.beta1, hp.beta2, hp.eps,
+                         int(hp.t), _ptr(norms), _ptr(xo), _ptr(mo), _ptr(vo))
+    return xo, mo, vo
 
 
 def _walk(fn, hp, xs, gs, ms, vs, mask):

@@ -145,6 +145,59 @@ void oracle_adamw_undo(int64_t n, const double *x_new, const double *g, const do
 }
 
 /* ------------------------------------------------------------------------- */
+/* LAMB for ONE tensor (one "layer").  The paper prints no LAMB algorithm; it says   */
+/* (section "Update-undo", Table 1) that LAMB adds a sum -- the L2 norms behind its   */
+/* trust ratio -- to Adam's elementwise operators, and that saving the norm (a scalar) */
+/* at step time makes the step invertible.  The step below is the published LAMB      */
+/* update (You et al. 2019, Alg. 2) with phi = identity:                               */
+/*   m_t, v_t, m^, v^ as in AdamW;  r = m^/(sqrt(v^)+eps);  u = r + lambda x_t;        */
+/*   q = ||x_t|| / ||u||  (q = 1 if either norm is 0);  x_{t+1} = x_t - eta q u.       */
+/* norms[0] = ||x_t||, norms[1] = ||u|| are returned: they are what the undo needs.    */
+void oracle_lamb_step(int64_t n, const double *x, const double *g, const double *m, const double *v,
+                      double eta, double lambda, double beta1, double beta2, double eps, int64_t t,
+                      double *x_new, double *m_new, double *v_new, double *norms)
+{
+    double bc1 = 1.0 - pow(beta1, (double)t);
+    double bc2 = 1.0 - pow(beta2, (double)t);
+    double sx = 0.0, su = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double mt = beta1 * m[i] + (1.0 - beta1) * g[i];
+        double vt = beta2 * v[i] + (1.0 - beta2) * (g[i] * g[i]);
+        double r = (mt / bc1) / (sqrt(vt / bc2) + eps);
+        double u = r + lambda * x[i];
+        m_new[i] = mt;
+        v_new[i] = vt;
+        x_new[i] = u;                 /* parked here until the norms are known */
+        sx += x[i] * x[i];
+        su += u * u;
+    }
+    double nx = sqrt(sx), nu = sqrt(su);
+    double q = (nx > 0.0 && nu > 0.0) ? nx / nu : 1.0;
+    for (int64_t i = 0; i < n; ++i)
+        x_new[i] = x[i] - eta * q * x_new[i];
+    norms[0] = nx;
+    norms[1] = nu;
+}
+
+/* Undo of the LAMB step with the two saved norms: q is rebuilt from them, r from the */
+/* new moments, and x_{t+1} = x_t (1 - eta q lambda) - eta q r is solved for x_t;      */
+/* the moments go back as in "Undo AdamW" (App. A).                                    */
+void oracle_lamb_undo(int64_t n, const double *x_new, const double *g, const double *m_new, const double *v_new,
+                      double eta, double lambda, double beta1, double beta2, double eps, int64_t t,
+                      const double *norms, double *x_old, double *m_old, double *v_old)
+{
+    double bc1 = 1.0 - pow(beta1, (double)t);
+    double bc2 = 1.0 - pow(beta2, (double)t);
+    double q = (norms[0] > 0.0 && norms[1] > 0.0) ? norms[0] / norms[1] : 1.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double r = (m_new[i] / bc1) / (sqrt(v_new[i] / bc2) + eps);
+        x_old[i] = (x_new[i] + eta * q * r) / (1.0 - eta * q * lambda);
+        m_old[i] = (m_new[i] - (1.0 - beta1) * g[i]) / beta1;
+        v_old[i] = (v_new[i] - (1.0 - beta2) * (g[i] * g[i])) / beta2;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* State digest of one shard of n 32-bit words (n < 2^32).                       */
 /* Not from the paper (which keeps a per-parameter "updated" flag): it is this   */
 /* library's stand-in for that flag.  Each word is tagged with its index inside  */

@@ -4,7 +4,7 @@ from fractions import Fraction
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
-_VECTORS = ("x", "g", "m", "v", "x_new", "m_new", "v_new")
+_VECTORS = ("x", "g", "m", "v", "x_new", "m_new", "v_new", "norms")
 
 
 def read_worked_examples():

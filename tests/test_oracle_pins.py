@@ -38,6 +38,17 @@ def test_worked_example_step_and_undo(case):
                eps=float(case.get("eps", 0)), t=int(case.get("t", 1)))
     f = lambda k: None if k not in case else np.array([float(q) for q in case[k]], F64)
     x, g, m, v = f("x"), f("g"), f("m"), f("v")
+    if case["kind"] == "lamb":
+        xn, mn, vn, norms = oracle.lamb_step(hp, x, g, m, v)
+        _close(norms, f("norms"), rtol=4e-16)
+        _close(xn, f("x_new"), rtol=4e-16, atol=1e-16)
+        _close(mn, f("m_new"), rtol=4e-16)
+        _close(vn, f("v_new"), rtol=4e-16)
+        xo, mo, vo = oracle.lamb_undo(hp, f("x_new"), g, f("m_new"), f("v_new"), f("norms"))
+        _close(xo, x, rtol=1e-15, atol=1e-15)
+        _close(mo, m, rtol=1e-15, atol=1e-15)
+        _close(vo, v, rtol=1e-15, atol=1e-15)
+        return
     xn, mn, vn = oracle.opt_step(hp, x, g, m, v)
     _close(xn, f("x_new"), rtol=4e-16, atol=1e-16)
     _close(mn, f("m_new"), rtol=4e-16, atol=1e-16)
@@ -333,6 +344,63 @@ def test_bf16_bits_widen_exactly():
     got = oracle.widen(bits)
     assert np.array_equal(got, want)
     assert np.signbit(got[3]) and got[3] == 0.0
+
+
+# --------------------------------------------------------------------------- LAMB
+def _adamw_direction(hp, x, g, m, v):
+    """u = r + lambda x, read off the (already pinned) AdamW step with eta = 1: x_new = x - u."""
+    one = Hyper("adamw", eta=1.0, lam=hp.lam, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, t=hp.t)
+    xn, mn, vn = oracle.opt_step(one, x, g, m, v)
+    return x - xn, mn, vn
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.01, 0.5])
+def test_lamb_is_adamw_with_the_trust_ratio_folded_into_the_learning_rate(lam):
+    # LAMB(eta) on one tensor = AdamW(eta * q), q = ||x|| / ||u||, with u and the norms taken from
+    # the pinned AdamW oracle and numpy, not from the LAMB code
+    x, g, m, v = _rand_state(21, n=1001)
+    hp = Hyper("lamb", eta=2e-3, lam=lam, beta1=0.9, beta2=0.999, eps=1e-6, t=12)
+    u, _, _ = _adamw_direction(hp, x, g, m, v)
+    nx, nu = np.sqrt(np.sum(x * x)), np.sqrt(np.sum(u * u))
+    xn, mn, vn, norms = oracle.lamb_step(hp, x, g, m, v)
+    _close(norms, [nx, nu], rtol=1e-10)          # u from x - x_new carries the subtraction's rounding
+    ref = oracle.opt_step(Hyper("adamw", eta=hp.eta * nx / nu, lam=lam, beta1=0.9, beta2=0.999, eps=1e-6, t=12), x, g, m, v)
+    _close(xn, ref[0], rtol=1e-11, atol=1e-15)
+    assert np.array_equal(mn, ref[1]) and np.array_equal(vn, ref[2])
+    # and the undo with the saved norms returns the state
+    xo, mo, vo = oracle.lamb_undo(hp, xn, g, mn, vn, norms)
+    _close(xo, x, rtol=1e-12, atol=1e-16)
+    _close(mo, m, rtol=1e-12, atol=1e-15 * np.abs(mn).max())
+    _close(vo, v, rtol=1e-12, atol=1e-15 * np.abs(vn).max())
+
+
+def test_lamb_zero_norm_falls_back_to_ratio_one():
+    _, g, m, v = _rand_state(22, n=64)
+    z = np.zeros_like(g)
+    hp = Hyper("lamb", eta=1e-3, lam=0.1, t=3)
+    xn, mn, vn, norms = oracle.lamb_step(hp, z, g, m, v)          # ||x|| = 0: q = 1, plain AdamW
+    ref = oracle.opt_step(Hyper("adamw", eta=1e-3, lam=0.1, t=3), z, g, m, v)
+    assert norms[0] == 0.0 and norms[1] > 0.0
+    assert np.array_equal(xn, ref[0])
+    xo, mo, vo = oracle.lamb_undo(hp, xn, g, mn, vn, norms)      # the undo applies the same fallback
+    _close(xo, z, rtol=0, atol=1e-18)
+    _close(mo, m, rtol=1e-12, atol=1e-15 * np.abs(mn).max())
+    x = np.ones_like(g)
+    xn, _, _, norms = oracle.lamb_step(Hyper("lamb", eta=1e-3, lam=0.0, t=3), x, z, z, v)   # u = 0: nothing moves
+    assert norms[1] == 0.0 and np.array_equal(xn, x)
+
+
+def test_lamb_layerwise_scaling():
+    # lambda = 0: scaling the parameters of the tensor by a power of two scales the whole update by it,
+    # bit for bit (the trust ratio carries the norm of x); scaling g, m, v as c, c, c^2 changes nothing
+    x, g, m, v = _rand_state(23, n=333)
+    v = v + 1e-12
+    hp = Hyper("lamb", eta=1e-2, lam=0.0, eps=0.0, t=5)
+    a = oracle.lamb_step(hp, x, g, m, v)
+    b = oracle.lamb_step(hp, 4 * x, g, m, v)
+    assert np.array_equal(4 * a[0], b[0]) and b[3][0] == 4 * a[3][0] and b[3][1] == a[3][1]
+    c = oracle.lamb_step(hp, x, 8 * g, 8 * m, 64 * v)
+    assert np.array_equal(a[0], c[0])
 
 
 # --------------------------------------------------------------------------- digest
