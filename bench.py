@@ -222,6 +222,27 @@ def main() -> int:
         log("[bench] ERROR: digest-derived mask differs from the step mask")
         return 1
 
+    # Outside the timed pass and outside `value`: LAMB step (three launches, 40 bytes per parameter)
+    # and its saved-norm undo (28 bytes per parameter), reported under "extras".
+    extras = {}
+    if not bf16:
+        hp_lamb = B.hparams("lamb", step=t_step, lr=2e-3, weight_decay=0.01, beta1=0.9, beta2=0.999, eps=1e-6)
+        norms = torch.zeros(2 * n_t, dtype=torch.float64, device="cuda")
+        for name, fn, bpe in (("lamb_step", lambda: B.swift_lamb_step(tl_adam, hp_lamb, norms), 40),
+                              ("lamb_undo", lambda: B.swift_lamb_undo(tl_adam, hp_lamb, norms), 28)):
+            reps = max(3, min(args.steps, 10))
+            fn()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            ev[0].record()
+            for k in range(reps):
+                fn()
+                ev[k + 1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[reps]) / reps
+            extras[name] = {"ms": round(ms, 4), "gparams_per_s": round(N / ms / 1e6, 2),
+                            "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
+            log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
+
     seg_ms = {s: 0.0 for s in segs}
     for ev in all_events:
         for k, s in enumerate(segs):
@@ -258,6 +279,7 @@ def main() -> int:
                      "traffic": traffic, "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
                      "gparams_per_s": dom_params / dom_ms / 1e6},
         "kernels": kernels,
+        "extras": extras,
     }
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")

@@ -50,7 +50,8 @@ typedef enum {
   SWIFT_SGDM = 0,  /* Alg. 1 / Alg. 2: SGD with momentum mu, dampening tau, coupled decay lambda.
                       mu = 0 is App. A's plain SGD with the damped gradient left in the m buffer. */
   SWIFT_ADAM = 1,  /* App. A "Adam" / "Undo Adam": decay coupled into the gradient, g' = g + lambda x */
-  SWIFT_ADAMW = 2  /* App. A "AdamW" / "Undo AdamW": decoupled decay, alpha = 1 */
+  SWIFT_ADAMW = 2, /* App. A "AdamW" / "Undo AdamW": decoupled decay, alpha = 1 */
+  SWIFT_LAMB = 3   /* LAMB with saved norms ("Update-undo" section, Table 1); swift_lamb_* entry points only */
 } swift_opt_kind;
 
 typedef enum { SWIFT_F32 = 0, SWIFT_BF16 = 1 } swift_dtype; /* gradients only */
@@ -118,6 +119,25 @@ int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
                          const uint8_t *device_mask, void *hip_stream);
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp,
                          const uint8_t *device_mask, void *hip_stream);
+
+/* LAMB.  The paper (section "Update-undo", Table 1) notes that LAMB adds a sum -- the L2 norms behind
+ * its per-tensor trust ratio -- to Adam's invertible elementwise operators, and that saving the norm
+ * (a scalar) at step time makes the step invertible; it prints no algorithm.  The step here is the
+ * published LAMB update (You et al. 2019) with phi = identity, per tensor of the list:
+ *   m, v as AdamW;  r = m^/(sqrt(v^)+eps);  u = r + lambda x;  q = ||x|| / ||u|| (1 if either norm is 0);
+ *   x <- x - eta q u
+ * swift_lamb_step writes norms_device[2i] = ||x_t||, norms_device[2i+1] = ||u|| (binary64) for every
+ * participating tensor i (entries of unmarked tensors are left alone; the sums are formed in a fixed
+ * order, so the values are reproducible bit for bit).  swift_lamb_undo takes those saved norms back:
+ *   x <- (x + eta q r)/(1 - eta q lambda);  m, v as "Undo AdamW" (App. A).
+ * hp->kind must be SWIFT_LAMB; beta1, beta2, eps as for Adam.  norms_device: DEVICE, 2*n doubles, 8-byte
+ * aligned.  If 1 - eta q lambda happens to be 0 for a tensor the undo yields Inf/NaN there (q lives on
+ * the device, so the host cannot refuse the call).  The step keeps per-list scratch for the partial
+ * sums (16 bytes per 1,024 elements): calls on the same list must not overlap in time. */
+int swift_lamb_step(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                    double *norms_device, void *hip_stream);
+int swift_lamb_undo(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                    const double *norms_device, void *hip_stream);
 
 /* 64-bit digests of raw 32-bit words.  This stands in for the paper's per-parameter "marked as
  * updated" flag (Implementation, "Update-undo"): a shard whose digest differs from the digest

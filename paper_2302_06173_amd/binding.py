@@ -16,9 +16,9 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libswift_undo.so")
 
 SWIFT_OK, SWIFT_EINVAL, SWIFT_ENOTINVERTIBLE, SWIFT_EHIP = 0, -1, -2, -3
-SWIFT_SGDM, SWIFT_ADAM, SWIFT_ADAMW = 0, 1, 2
+SWIFT_SGDM, SWIFT_ADAM, SWIFT_ADAMW, SWIFT_LAMB = 0, 1, 2, 3
 SWIFT_F32, SWIFT_BF16 = 0, 1
-KINDS = {"sgdm": SWIFT_SGDM, "adam": SWIFT_ADAM, "adamw": SWIFT_ADAMW}
+KINDS = {"sgdm": SWIFT_SGDM, "adam": SWIFT_ADAM, "adamw": SWIFT_ADAMW, "lamb": SWIFT_LAMB}
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -44,6 +44,9 @@ _P = ctypes.c_void_p
 for _name in ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask"):
     getattr(_lib, _name).argtypes = [ctypes.POINTER(SwiftTensorList), ctypes.POINTER(SwiftHparams), _P, _P]
     getattr(_lib, _name).restype = ctypes.c_int
+for _name in ("swift_lamb_step", "swift_lamb_undo"):
+    getattr(_lib, _name).argtypes = [ctypes.POINTER(SwiftTensorList), ctypes.POINTER(SwiftHparams), _P, _P, _P]
+    getattr(_lib, _name).restype = ctypes.c_int
 _lib.swift_state_digest.argtypes = [ctypes.c_int64, ctypes.POINTER(_P), ctypes.POINTER(ctypes.c_int64),
                                     ctypes.c_int64, _P, _P]
 _lib.swift_state_digest.restype = ctypes.c_int
@@ -59,6 +62,7 @@ _lib.swift_last_error.argtypes = []
 _lib.swift_last_error.restype = ctypes.c_char_p
 
 EXPORTS = ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask",
+           "swift_lamb_step", "swift_lamb_undo",
            "swift_state_digest", "swift_digest_count", "swift_mask_from_digests", "swift_stream_copy",
            "swift_shutdown", "swift_last_error")
 
@@ -169,6 +173,29 @@ def swift_opt_step_dmask(tl: TensorList, hp: SwiftHparams, device_mask: torch.Te
 def swift_opt_undo_dmask(tl: TensorList, hp: SwiftHparams, device_mask: torch.Tensor, stream=None) -> None:
     _check(_lib.swift_opt_undo_dmask(ctypes.byref(tl.c), ctypes.byref(hp), _dmask_ptr(device_mask, tl.n),
                                      _stream_handle(stream)))
+
+
+def _norms_ptr(norms: torch.Tensor, n: int) -> int:
+    if norms.dtype != torch.float64 or not norms.is_cuda or not norms.is_contiguous() or norms.numel() != 2 * n:
+        raise ValueError("norms must be a contiguous CUDA float64 tensor with two entries per tensor")
+    return norms.data_ptr()
+
+
+def swift_lamb_step(tl: TensorList, hp: SwiftHparams, norms: Optional[torch.Tensor] = None, host_mask=None,
+                    stream=None) -> torch.Tensor:
+    """LAMB step; returns the float64 CUDA tensor of saved norms (||x_t||, ||u|| per tensor)."""
+    if norms is None:
+        norms = torch.zeros(2 * tl.n, dtype=torch.float64, device="cuda")
+    keep, p = _host_mask(host_mask, tl.n)
+    _check(_lib.swift_lamb_step(ctypes.byref(tl.c), ctypes.byref(hp), p, _norms_ptr(norms, tl.n) if tl.n else None,
+                                _stream_handle(stream)))
+    return norms
+
+
+def swift_lamb_undo(tl: TensorList, hp: SwiftHparams, norms: torch.Tensor, host_mask=None, stream=None) -> None:
+    keep, p = _host_mask(host_mask, tl.n)
+    _check(_lib.swift_lamb_undo(ctypes.byref(tl.c), ctypes.byref(hp), p, _norms_ptr(norms, tl.n) if tl.n else None,
+                                _stream_handle(stream)))
 
 
 class BufferList:

@@ -18,6 +18,7 @@
 #include "swift_undo.h"
 #include "opt_kernels.hpp"
 #include "digest_kernels.hpp"
+#include "lamb_kernels.hpp"
 
 namespace swift {
 namespace {
@@ -85,6 +86,14 @@ struct Plan {
   uint32_t n_chunks = 0;
   uint32_t chunk_elems = 0;
   uint64_t n_out = 0;            // digest plans: number of outputs
+  // optimizer plans: where each tensor of the caller's list sits in the chunk table
+  std::vector<uint64_t> t_first_chunk, t_numel;   // t_numel[i] = 0 for empty or unmarked tensors
+  std::vector<uint8_t> t_active;
+  // LAMB only, created on first use (guarded by lamb_mu): tensor spans and per-tile partial sums
+  std::mutex lamb_mu;
+  void *lamb_spans = nullptr;
+  void *lamb_partial = nullptr;
+  uint32_t lamb_tile_elems = 0;
   const void *descs() const { return dev_mem; }
   const void *chunks() const { return static_cast<const char *>(dev_mem) + desc_bytes; }
   ~Plan() {
@@ -92,6 +101,8 @@ struct Plan {
       int cur = -1;
       if (hipGetDevice(&cur) == hipSuccess && cur != device) (void)hipSetDevice(device);
       (void)hipFree(dev_mem);    // synchronises the device: no kernel still reads the table
+      if (lamb_spans) (void)hipFree(lamb_spans);
+      if (lamb_partial) (void)hipFree(lamb_partial);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     }
   }
@@ -186,13 +197,14 @@ uint32_t lds_cap_bytes(const DeviceInfo &info, const Tuning &t) {
   return bytes > 65536u ? 65536u : bytes;
 }
 
-// Chunk length (a power of two, at least one tile).  Long chunks keep the table small; short
-// ones waste fewer idle workgroups on the many tiny tensors of a small model.
-uint32_t pick_chunk_elems(uint32_t tile_elems, uint64_t total_elems) {
+// Chunk length: a power of two that is a multiple of every compiled tile (at most 1,024 elements).
+// Long chunks keep the table small; short ones waste fewer idle workgroups on the many tiny
+// tensors of a small model.
+constexpr uint32_t kMaxTileElems = 4096;
+uint32_t pick_chunk_elems(uint64_t total_elems) {
   long forced = env_long("SWIFT_CHUNK_ELEMS", 0);              // tuning knob for sweeps
-  if (forced >= (long)tile_elems && forced <= (1l << 22) && (forced & (forced - 1)) == 0) return (uint32_t)forced;
-  const uint32_t ce = total_elems >= (1ull << 28) ? 65536u : 16384u;
-  return tile_elems > ce ? tile_elems : ce;
+  if (forced >= (long)kMaxTileElems && forced <= (1l << 22) && (forced & (forced - 1)) == 0) return (uint32_t)forced;
+  return total_elems >= (1ull << 28) ? 65536u : 16384u;
 }
 
 int upload_plan(Plan &plan, const void *descs, size_t desc_bytes, const void *chunks, size_t n_chunks,
@@ -219,7 +231,7 @@ struct Interval {
 
 int validate_hparams(const swift_hparams *hp, bool undo, OptConsts *c) {
   if (!hp) return fail(SWIFT_EINVAL, "hparams is NULL");
-  if (hp->kind < SWIFT_SGDM || hp->kind > SWIFT_ADAMW) return fail(SWIFT_EINVAL, "unknown optimizer kind %d", hp->kind);
+  if (hp->kind < SWIFT_SGDM || hp->kind > SWIFT_LAMB) return fail(SWIFT_EINVAL, "unknown optimizer kind %d", hp->kind);
   if (hp->grad_dtype != SWIFT_F32 && hp->grad_dtype != SWIFT_BF16)
     return fail(SWIFT_EINVAL, "unknown gradient dtype %d", hp->grad_dtype);
   if (hp->step < 1) return fail(SWIFT_EINVAL, "step must be >= 1 (got %lld)", (long long)hp->step);
@@ -281,7 +293,7 @@ int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
 }
 
 int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, int dev,
-                   uint32_t tile_elems, std::shared_ptr<Plan> *out) {
+                   std::shared_ptr<Plan> *out) {
   const bool hasv = hp->kind != SWIFT_SGDM;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16;
   std::string key;
@@ -291,7 +303,6 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   key_add(key, (uint8_t)hasv);
   key_add(key, (uint8_t)bf16);
   key_add(key, l->n);
-  key_add(key, tile_elems);
   key_add(key, env_long("SWIFT_CHUNK_ELEMS", 0));
   for (int64_t i = 0; i < l->n; ++i) {
     const uint8_t on = host_mask ? (host_mask[i] != 0) : 1;
@@ -338,14 +349,20 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   auto plan = std::make_shared<Plan>();
   plan->key = std::move(key);
   plan->device = dev;
-  plan->chunk_elems = pick_chunk_elems(tile_elems, total);
+  plan->chunk_elems = pick_chunk_elems(total);
   const uint64_t ce = plan->chunk_elems;
   std::vector<ChunkDesc> chunks;
   chunks.reserve((size_t)(total / ce) + (size_t)l->n);
+  plan->t_first_chunk.assign((size_t)l->n, 0);
+  plan->t_numel.assign((size_t)l->n, 0);
+  plan->t_active.assign((size_t)l->n, 0);
   for (int64_t i = 0; i < l->n; ++i) {
     if (host_mask && !host_mask[i]) continue;
+    plan->t_active[(size_t)i] = 1;
+    plan->t_first_chunk[(size_t)i] = chunks.size();
     const uint64_t n = (uint64_t)l->numel[i];
     if (n == 0) continue;
+    plan->t_numel[(size_t)i] = n;
     char *x = static_cast<char *>(l->param[i]), *m = static_cast<char *>(l->m[i]);
     char *v = hasv ? static_cast<char *>(l->v[i]) : nullptr;
     const char *g = static_cast<const char *>(l->grad[i]);
@@ -400,6 +417,8 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   OptConsts c;
   int rc = validate_hparams(hp, undo, &c);
   if (rc) return rc;
+  if (hp->kind == SWIFT_LAMB)
+    return fail(SWIFT_EINVAL, "LAMB needs the saved norms: use swift_lamb_step / swift_lamb_undo");
   if ((rc = validate_list(l, hp))) return rc;
   if (want_dmask && !device_mask && l->n > 0) return fail(SWIFT_EINVAL, "device mask is NULL");
   if (l->n == 0) return SWIFT_OK;
@@ -413,7 +432,7 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   const uint32_t tile_elems = (uint32_t)tune.u * (uint32_t)tune.block * 4u;
   if (want_dmask && (rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
   std::shared_ptr<Plan> plan;
-  if ((rc = build_opt_plan(l, hp, host_mask, dev, tile_elems, &plan))) return rc;
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
   if (plan->n_chunks == 0) return SWIFT_OK;
   uint32_t tpc_shift = 0;
   while ((tile_elems << tpc_shift) < plan->chunk_elems) ++tpc_shift;
@@ -439,6 +458,93 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
                      static_cast<hipStream_t>(stream), static_cast<const ChunkDesc *>(plan->chunks()), n_groups,
                      tpc_shift, grp_shift, device_mask, c);
   SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// LAMB: step = moments + partial sums, norms, apply; undo = one launch.
+constexpr int kLambU = 4, kLambBlock = 64;     // pass 1 tile: 1,024 elements, one partial sum each
+
+int lamb_prepare(Plan &plan, uint32_t tile_elems) {
+  std::lock_guard<std::mutex> lock(plan.lamb_mu);
+  if (plan.lamb_spans) return SWIFT_OK;
+  const uint64_t tpc = plan.chunk_elems / tile_elems;
+  std::vector<TensorSpan> spans(plan.t_numel.size());
+  for (size_t i = 0; i < spans.size(); ++i) {
+    spans[i].first_slot = plan.t_first_chunk[i] * tpc;
+    spans[i].n_slots = (plan.t_numel[i] + tile_elems - 1) / tile_elems;   // only the last chunk is short
+    spans[i].active = plan.t_active[i];
+    spans[i].pad = 0;
+  }
+  void *dspans = nullptr, *dpartial = nullptr;
+  SWIFT_HIP(hipMalloc(&dspans, std::max<size_t>(spans.size(), 1) * sizeof(TensorSpan)));
+  hipError_t e = hipMemcpy(dspans, spans.data(), spans.size() * sizeof(TensorSpan), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMalloc(&dpartial, std::max<uint64_t>((uint64_t)plan.n_chunks * tpc, 1) * sizeof(double2));
+  if (e != hipSuccess) {
+    (void)hipFree(dspans);
+    return fail(SWIFT_EHIP, "LAMB scratch allocation failed: %s", hipGetErrorName(e));
+  }
+  plan.lamb_partial = dpartial;
+  plan.lamb_tile_elems = tile_elems;
+  plan.lamb_spans = dspans;
+  return SWIFT_OK;
+}
+
+uint32_t shift_for(uint32_t tile_elems, uint32_t chunk_elems) {
+  uint32_t s = 0;
+  while ((tile_elems << s) < chunk_elems) ++s;
+  return s;
+}
+
+int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, double *norms,
+              bool undo, void *stream_) {
+  OptConsts c;
+  int rc = validate_hparams(hp, undo, &c);
+  if (rc) return rc;
+  if (hp->kind != SWIFT_LAMB) return fail(SWIFT_EINVAL, "swift_lamb_* needs kind = SWIFT_LAMB");
+  if ((rc = validate_list(l, hp))) return rc;
+  if (l->n == 0) return SWIFT_OK;
+  if (!norms) return fail(SWIFT_EINVAL, "norms_device is NULL");
+  if ((uintptr_t)norms & 7) return fail(SWIFT_EINVAL, "norms_device is not 8-byte aligned");
+  int dev = -1;
+  SWIFT_HIP(hipGetDevice(&dev));
+  DeviceInfo info;
+  if ((rc = device_info(dev, &info))) return rc;
+  if ((rc = check_device_range(norms, (size_t)l->n * 16, dev, "norms_device", 0))) return rc;
+  const bool bf16 = hp->grad_dtype == SWIFT_BF16;
+  std::shared_ptr<Plan> plan;
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const uint32_t tile1 = kLambU * kLambBlock * 4u, tile3 = 1u * 64u * 4u;
+  const uint32_t s1 = shift_for(tile1, plan->chunk_elems), s3 = shift_for(tile3, plan->chunk_elems);
+  const uint64_t slots1 = (uint64_t)plan->n_chunks << s1, slots3 = (uint64_t)plan->n_chunks << s3;
+  const Tuning t1{kLambU, kLambBlock, (int)env_long("SWIFT_LAMB_WAVES_P1", SWIFT_LAMB_WAVES_P1)};
+  const Tuning t3{1, 64, (int)env_long("SWIFT_LAMB_WAVES_P3", SWIFT_LAMB_WAVES_P3)};
+  const Tuning tu = opt_tuning(SWIFT_ADAMW, bf16);
+  const ChunkDesc *chunks = static_cast<const ChunkDesc *>(plan->chunks());
+  if (undo) {
+    if (plan->n_chunks == 0) return SWIFT_OK;
+    const auto k = bf16 ? lamb_undo_kernel<true, 1, 64> : lamb_undo_kernel<false, 1, 64>;
+    hipLaunchKernelGGL(k, dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64), lds_cap_bytes(info, tu),
+                       stream, chunks, slots3, s3, c, static_cast<const double *>(norms));
+    SWIFT_HIP(hipGetLastError());
+    return SWIFT_OK;
+  }
+  if ((rc = lamb_prepare(*plan, tile1))) return rc;
+  if (plan->n_chunks) {
+    const auto k1 = bf16 ? lamb_moments_kernel<true, kLambU, kLambBlock> : lamb_moments_kernel<false, kLambU, kLambBlock>;
+    hipLaunchKernelGGL(k1, dim3((uint32_t)std::min<uint64_t>(slots1, 0x7fffffffull)), dim3(kLambBlock),
+                       lds_cap_bytes(info, t1), stream, chunks, slots1, s1, c, static_cast<double2 *>(plan->lamb_partial));
+    SWIFT_HIP(hipGetLastError());
+  }
+  hipLaunchKernelGGL(lamb_norms_kernel, dim3((uint32_t)l->n), dim3(kThreads), 0, stream,
+                     static_cast<const TensorSpan *>(plan->lamb_spans), static_cast<const double2 *>(plan->lamb_partial), norms);
+  SWIFT_HIP(hipGetLastError());
+  if (plan->n_chunks) {
+    hipLaunchKernelGGL((lamb_apply_kernel<1, 64>), dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64),
+                       lds_cap_bytes(info, t3), stream, chunks, slots3, s3, c, static_cast<const double *>(norms));
+    SWIFT_HIP(hipGetLastError());
+  }
   return SWIFT_OK;
 }
 
@@ -556,6 +662,16 @@ int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
                          void *hip_stream) {
   return opt_call(list, hp, nullptr, device_mask, true, true, hip_stream);
+}
+
+int swift_lamb_step(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                    double *norms_device, void *hip_stream) {
+  return lamb_call(list, hp, host_mask, norms_device, false, hip_stream);
+}
+
+int swift_lamb_undo(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                    const double *norms_device, void *hip_stream) {
+  return lamb_call(list, hp, host_mask, const_cast<double *>(norms_device), true, hip_stream);
 }
 
 int64_t swift_digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems) {

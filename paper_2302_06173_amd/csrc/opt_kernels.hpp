@@ -28,6 +28,8 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #define SWIFT_DEFAULT_WAVES_PER_CU 11
 #define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
 #define SWIFT_DEFAULT_GROUP_SHIFT_DMASK 0
+#define SWIFT_LAMB_WAVES_P1 6           // LAMB pass 1 (U = 4): wavefronts per CU
+#define SWIFT_LAMB_WAVES_P3 24          // LAMB pass 3 (3 streams in, 1 out)
 #define SWIFT_DEFAULT_DMASK_WGS_PER_CU 16384
 #endif
 #ifndef SWIFT_NT
@@ -148,15 +150,27 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
   }
 }
 
+// An "op" tells process_tile which streams a kernel moves and what to do with one element:
+//   kLoadG, kHasV          gradient / second moment are read
+//   kStoreX, kStoreM, kStoreV   streams written back
+//   elem(x, g, m, v)       the element arithmetic (may also accumulate into members of the op)
 template <int KIND, bool UNDO>
-__device__ __forceinline__ void update_vec4(f32x4 &x, const f32x4 &g, f32x4 &m, f32x4 &v, const OptConsts &c) {
+struct OptOp {             // optimizer step or undo of one element
+  static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
+  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV;
+  const OptConsts &c;
+  __device__ __forceinline__ void elem(float &x, float g, float &m, float &v) { update_elem<KIND, UNDO>(x, g, m, v, c); }
+};
+
+template <typename Op>
+__device__ __forceinline__ void update_vec4(Op &op, f32x4 &x, const f32x4 &g, f32x4 &m, f32x4 &v) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    float xe = x[k], me = m[k], ve = (KIND == kSGDM) ? 0.f : v[k];
-    update_elem<KIND, UNDO>(xe, g[k], me, ve, c);
+    float xe = x[k], me = m[k], ve = Op::kHasV ? v[k] : 0.f;
+    op.elem(xe, Op::kLoadG ? g[k] : 0.f, me, ve);
     x[k] = xe;
     m[k] = me;
-    if constexpr (KIND != kSGDM) v[k] = ve;
+    if constexpr (Op::kHasV) v[k] = ve;
   }
 }
 
@@ -182,23 +196,31 @@ __device__ __forceinline__ float load_grad1(const void *g, int64_t i) {
   else return ld<false>(reinterpret_cast<const float *>(g) + i);
 }
 
+// One element through 4-byte accesses (ragged tails and unaligned tensors).
+template <typename Op, bool BF16G>
+__device__ __forceinline__ void process_scalar(Op &op, const ChunkDesc &d, uint32_t e) {
+  float xe = ld<false>(d.x + e), me = ld<false>(d.m + e), ve = 0.f, ge = 0.f;
+  if constexpr (Op::kHasV) ve = ld<false>(d.v + e);
+  if constexpr (Op::kLoadG) ge = load_grad1<BF16G>(d.g, e);
+  op.elem(xe, ge, me, ve);
+  if constexpr (Op::kStoreX) st<false>(d.x + e, xe);
+  if constexpr (Op::kStoreM) st<false>(d.m + e, me);
+  if constexpr (Op::kStoreV) st<false>(d.v + e, ve);
+}
+
 // One tile: U*BLOCK 16-byte vectors (U*BLOCK*4 elements) of one chunk, starting at element
 // ti * U*BLOCK*4 of the chunk (the caller has checked that this is inside the chunk).
-template <int KIND, bool UNDO, bool BF16G, int U, int BLOCK>
-__device__ __forceinline__ void process_tile(const ChunkDesc &d, uint32_t ti, uint32_t tid, const OptConsts &c) {
-  constexpr bool HASV = (KIND != kSGDM);
+template <typename Op, bool BF16G, int U, int BLOCK>
+__device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_t ti, uint32_t tid) {
+  constexpr bool HASV = Op::kHasV;
   constexpr uint32_t TILE4 = U * BLOCK;                          // vectors per tile
   const uint32_t len = d.len;
-  float *__restrict__ xp = d.x;
-  float *__restrict__ mp = d.m;
-  float *__restrict__ vp = d.v;
-  const void *gp = d.g;
   if (d.vec_ok) {
     // chunk starts are multiples of 4 elements, so chunks keep their tensor's 16-byte alignment
     const uint32_t n4 = len >> 2;
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(xp, n4 * 16u), rm = make_rsrc(mp, n4 * 16u);
-    const __amdgpu_buffer_rsrc_t rv = make_rsrc(vp, HASV ? n4 * 16u : 0u);
-    const __amdgpu_buffer_rsrc_t rg = make_rsrc(gp, n4 * (BF16G ? 8u : 16u));
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(d.x, n4 * 16u), rm = make_rsrc(d.m, n4 * 16u);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(d.v, HASV ? n4 * 16u : 0u);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc(d.g, Op::kLoadG ? n4 * (BF16G ? 8u : 16u) : 0u);
     const uint32_t j0 = ti * TILE4;
     if (j0 + TILE4 <= n4) {                                      // full tile: no predicates
       f32x4 xr[U], gr[U], mr[U], vr[U];
@@ -206,49 +228,47 @@ __device__ __forceinline__ void process_tile(const ChunkDesc &d, uint32_t ti, ui
       for (int u = 0; u < U; ++u) {
         const uint32_t j = j0 + u * BLOCK + tid;
         xr[u] = buf_ld4(rx, j * 16u);
-        gr[u] = load_grad4<BF16G>(rg, j);
+        gr[u] = Op::kLoadG ? load_grad4<BF16G>(rg, j) : f32x4{0.f, 0.f, 0.f, 0.f};
         mr[u] = buf_ld4(rm, j * 16u);
-        if constexpr (HASV) vr[u] = buf_ld4(rv, j * 16u);
+        vr[u] = HASV ? buf_ld4(rv, j * 16u) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t j = j0 + u * BLOCK + tid;
-        update_vec4<KIND, UNDO>(xr[u], gr[u], mr[u], vr[u], c);
-        buf_st4(rx, j * 16u, xr[u]);
-        buf_st4(rm, j * 16u, mr[u]);
-        if constexpr (HASV) buf_st4(rv, j * 16u, vr[u]);
+        update_vec4(op, xr[u], gr[u], mr[u], vr[u]);
+        if constexpr (Op::kStoreX) buf_st4(rx, j * 16u, xr[u]);
+        if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr[u]);
+        if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr[u]);
       }
     } else {                                                     // ragged end of a tensor
       for (uint32_t j = j0 + tid; j < n4; j += BLOCK) {
-        f32x4 xr = buf_ld4(rx, j * 16u), gr = load_grad4<BF16G>(rg, j), mr = buf_ld4(rm, j * 16u), vr;
-        if constexpr (HASV) vr = buf_ld4(rv, j * 16u);
-        update_vec4<KIND, UNDO>(xr, gr, mr, vr, c);
-        buf_st4(rx, j * 16u, xr);
-        buf_st4(rm, j * 16u, mr);
-        if constexpr (HASV) buf_st4(rv, j * 16u, vr);
+        f32x4 xr = buf_ld4(rx, j * 16u), mr = buf_ld4(rm, j * 16u);
+        f32x4 gr = Op::kLoadG ? load_grad4<BF16G>(rg, j) : f32x4{0.f, 0.f, 0.f, 0.f};
+        f32x4 vr = HASV ? buf_ld4(rv, j * 16u) : f32x4{0.f, 0.f, 0.f, 0.f};
+        update_vec4(op, xr, gr, mr, vr);
+        if constexpr (Op::kStoreX) buf_st4(rx, j * 16u, xr);
+        if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr);
+        if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr);
       }
       const uint32_t e = (n4 << 2) + tid;                        // last numel % 4 elements
-      if (e < len) {                                             // (they start inside this tile)
-        float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
-        if constexpr (HASV) ve = ld<false>(vp + e);
-        update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
-        st<false>(xp + e, xe);
-        st<false>(mp + e, me);
-        if constexpr (HASV) st<false>(vp + e, ve);
-      }
+      if (e < len) process_scalar<Op, BF16G>(op, d, e);          // (they start inside this tile)
     }
   } else {                                                       // unaligned tensor: 4-byte accesses
     const uint32_t e0 = ti * (TILE4 * 4u);
     const uint32_t e1 = (e0 + TILE4 * 4u < len) ? e0 + TILE4 * 4u : len;
-    for (uint32_t e = e0 + tid; e < e1; e += BLOCK) {
-      float xe = ld<false>(xp + e), me = ld<false>(mp + e), ve = 0.f;
-      if constexpr (HASV) ve = ld<false>(vp + e);
-      update_elem<KIND, UNDO>(xe, load_grad1<BF16G>(gp, e), me, ve, c);
-      st<false>(xp + e, xe);
-      st<false>(mp + e, me);
-      if constexpr (HASV) st<false>(vp + e, ve);
-    }
+    for (uint32_t e = e0 + tid; e < e1; e += BLOCK) process_scalar<Op, BF16G>(op, d, e);
   }
+}
+
+// The device mask byte of a tensor, read through the scalar cache: the aligned 32-bit word that
+// holds it is fetched from the constant address space (the word lies in the same page as the
+// byte, so this never leaves the caller's mapping; the mask is not written while the kernel
+// runs, which is what the constant space requires).
+__device__ __forceinline__ bool tensor_is_marked(const uint8_t *dmask, uint32_t tensor) {
+  const uintptr_t a = (uintptr_t)(dmask + tensor);
+  typedef const __attribute__((address_space(4))) uint32_t *const_u32_ptr;
+  const uint32_t word = *(const_u32_ptr)(a & ~(uintptr_t)3);
+  return ((word >> (8u * (uint32_t)(a & 3u))) & 0xFFu) != 0;
 }
 
 // One workgroup per group of 2^grp_shift consecutive tiles (normally one tile).  A chunk is up to
@@ -270,6 +290,7 @@ opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_groups, uint32_t tpc
            const uint8_t *__restrict__ dmask, const OptConsts c) {
   constexpr uint32_t TILE = U * BLOCK * 4u;                      // elements per tile
   const uint32_t tid = threadIdx.x;
+  OptOp<KIND, UNDO> op{c};
   // The host launches at most n_groups workgroups, so the first pass needs no bounds test (and no
   // wait for n_groups before the chunk entry can be fetched).
   uint64_t grp = blockIdx.x;
@@ -280,20 +301,12 @@ opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_groups, uint32_t tpc
     // (the pointer test is always true for a chunk with elements; it makes the compiler fetch the
     //  whole entry with one round of scalar loads instead of the length first and the pointers later)
     if (ti0 * TILE >= d.len || d.x == nullptr) continue;         // short last chunk: nothing here
-    if (dmask != nullptr) {
-      // the mask byte through the scalar cache: read the aligned 32-bit word that holds it (the
-      // word lies in the same page as the byte, so this never leaves the caller's mapping; the
-      // mask is not written while this kernel runs, which is what the constant space requires)
-      const uintptr_t a = (uintptr_t)(dmask + d.tensor);
-      typedef const __attribute__((address_space(4))) uint32_t *const_u32_ptr;   // constant space: s_load
-      const uint32_t word = *(const_u32_ptr)(a & ~(uintptr_t)3);
-      if (((word >> (8u * (uint32_t)(a & 3u))) & 0xFFu) == 0) continue;
-    }
+    if (dmask != nullptr && !tensor_is_marked(dmask, d.tensor)) continue;
     const uint32_t n_tiles = 1u << grp_shift;
     for (uint32_t k = 0; k < n_tiles; ++k) {
       const uint32_t ti = ti0 + k;
       if (ti * TILE >= d.len) break;
-      process_tile<KIND, UNDO, BF16G, U, BLOCK>(d, ti, tid, c);
+      process_tile<OptOp<KIND, UNDO>, BF16G, U, BLOCK>(op, d, ti, tid);
     }
   } while ((grp += gridDim.x) < n_groups);
 }
