@@ -243,6 +243,23 @@ def main() -> int:
                             "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
             log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
 
+    hp_w = hps["adamw"]
+    dig = torch.zeros(3 * n_t, dtype=torch.int64, device="cuda")
+    for name, fn, bpe in (("adamw_step_with_digest", lambda: B.swift_opt_step_digest(tl_adam, hp_w, dig), 24 + g_bytes),
+                          ("adamw_undo_with_digest", lambda: B.swift_opt_undo_digest(tl_adam, hp_w, dig), 24 + g_bytes)):
+        reps = max(3, min(args.steps, 10))
+        fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for k in range(reps):
+            fn()
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[reps]) / reps
+        extras[name] = {"ms": round(ms, 4), "gparams_per_s": round(N / ms / 1e6, 2),
+                        "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
+        log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
+
     seg_ms = {s: 0.0 for s in segs}
     for ev in all_events:
         for k, s in enumerate(segs):

@@ -120,6 +120,20 @@ int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp,
                          const uint8_t *device_mask, void *hip_stream);
 
+/* swift_opt_step / swift_opt_undo that also return the digests of the state they leave behind, at no
+ * extra HBM traffic: digests_device[g * n + i] is the digest of tensor i's theta (g = 0), m (g = 1) and
+ * v (g = 2; SGDM has g = 0, 1 only), one shard per tensor, identical to what swift_state_digest writes
+ * for the buffer order theta_0..theta_{n-1}, m_0.., v_0.. with shard_elems = 0.  A training loop keeps
+ * the digests of the last completed iteration this way; after a failure one swift_state_digest pass and
+ * swift_mask_from_digests tell which tensors hold stepped bits (the role of the paper's per-parameter
+ * "updated" flag, Implementation, "Update-undo").  Entries of unmarked tensors are left alone.  Every
+ * tensor must have fewer than 2^32 elements.  digests_device: DEVICE, 3n (2n for SGDM) entries, 8-byte
+ * aligned.  The call keeps per-list scratch (24 bytes per chunk): calls on one list must not overlap. */
+int swift_opt_step_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                          uint64_t *digests_device, void *hip_stream);
+int swift_opt_undo_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                          uint64_t *digests_device, void *hip_stream);
+
 /* LAMB.  The paper (section "Update-undo", Table 1) notes that LAMB adds a sum -- the L2 norms behind
  * its per-tensor trust ratio -- to Adam's invertible elementwise operators, and that saving the norm
  * (a scalar) at step time makes the step invertible; it prints no algorithm.  The step here is the

@@ -44,7 +44,7 @@ _P = ctypes.c_void_p
 for _name in ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask"):
     getattr(_lib, _name).argtypes = [ctypes.POINTER(SwiftTensorList), ctypes.POINTER(SwiftHparams), _P, _P]
     getattr(_lib, _name).restype = ctypes.c_int
-for _name in ("swift_lamb_step", "swift_lamb_undo"):
+for _name in ("swift_lamb_step", "swift_lamb_undo", "swift_opt_step_digest", "swift_opt_undo_digest"):
     getattr(_lib, _name).argtypes = [ctypes.POINTER(SwiftTensorList), ctypes.POINTER(SwiftHparams), _P, _P, _P]
     getattr(_lib, _name).restype = ctypes.c_int
 _lib.swift_state_digest.argtypes = [ctypes.c_int64, ctypes.POINTER(_P), ctypes.POINTER(ctypes.c_int64),
@@ -62,7 +62,7 @@ _lib.swift_last_error.argtypes = []
 _lib.swift_last_error.restype = ctypes.c_char_p
 
 EXPORTS = ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask",
-           "swift_lamb_step", "swift_lamb_undo",
+           "swift_lamb_step", "swift_lamb_undo", "swift_opt_step_digest", "swift_opt_undo_digest",
            "swift_state_digest", "swift_digest_count", "swift_mask_from_digests", "swift_stream_copy",
            "swift_shutdown", "swift_last_error")
 
@@ -196,6 +196,30 @@ def swift_lamb_undo(tl: TensorList, hp: SwiftHparams, norms: torch.Tensor, host_
     keep, p = _host_mask(host_mask, tl.n)
     _check(_lib.swift_lamb_undo(ctypes.byref(tl.c), ctypes.byref(hp), p, _norms_ptr(norms, tl.n) if tl.n else None,
                                 _stream_handle(stream)))
+
+
+def _fused(fn, tl: TensorList, hp: SwiftHparams, digests, host_mask, stream) -> torch.Tensor:
+    n_groups = 2 if hp.kind == SWIFT_SGDM else 3
+    if digests is None:
+        digests = torch.zeros(n_groups * tl.n, dtype=torch.int64, device="cuda")
+    elif digests.dtype != torch.int64 or not digests.is_cuda or not digests.is_contiguous() \
+            or digests.numel() != n_groups * tl.n:
+        raise ValueError(f"digests must be a contiguous CUDA int64 tensor of {n_groups * tl.n} elements")
+    keep, p = _host_mask(host_mask, tl.n)
+    _check(fn(ctypes.byref(tl.c), ctypes.byref(hp), p, digests.data_ptr() if tl.n else None, _stream_handle(stream)))
+    return digests
+
+
+def swift_opt_step_digest(tl: TensorList, hp: SwiftHparams, digests: Optional[torch.Tensor] = None, host_mask=None,
+                          stream=None) -> torch.Tensor:
+    """Step, and the per-tensor digests (theta.., m.., v..) of the state it leaves (int64 CUDA tensor)."""
+    return _fused(_lib.swift_opt_step_digest, tl, hp, digests, host_mask, stream)
+
+
+def swift_opt_undo_digest(tl: TensorList, hp: SwiftHparams, digests: Optional[torch.Tensor] = None, host_mask=None,
+                          stream=None) -> torch.Tensor:
+    """Undo, and the per-tensor digests of the state it leaves."""
+    return _fused(_lib.swift_opt_undo_digest, tl, hp, digests, host_mask, stream)
 
 
 class BufferList:

@@ -19,6 +19,7 @@
 #include "opt_kernels.hpp"
 #include "digest_kernels.hpp"
 #include "lamb_kernels.hpp"
+#include "fused_kernels.hpp"
 
 namespace swift {
 namespace {
@@ -94,6 +95,9 @@ struct Plan {
   void *lamb_spans = nullptr;
   void *lamb_partial = nullptr;
   uint32_t lamb_tile_elems = 0;
+  // fused step/undo + digest only, created on first use (guarded by lamb_mu): chunk spans and slots
+  void *fused_spans = nullptr;
+  void *fused_slots = nullptr;
   const void *descs() const { return dev_mem; }
   const void *chunks() const { return static_cast<const char *>(dev_mem) + desc_bytes; }
   ~Plan() {
@@ -103,6 +107,8 @@ struct Plan {
       (void)hipFree(dev_mem);    // synchronises the device: no kernel still reads the table
       if (lamb_spans) (void)hipFree(lamb_spans);
       if (lamb_partial) (void)hipFree(lamb_partial);
+      if (fused_spans) (void)hipFree(fused_spans);
+      if (fused_slots) (void)hipFree(fused_slots);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     }
   }
@@ -377,7 +383,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
       d.len = (uint32_t)std::min<uint64_t>(ce, n - off);
       d.tensor = (uint32_t)i;
       d.vec_ok = vec_ok;
-      d.pad = 0;
+      d.elem0 = (uint32_t)off;
       chunks.push_back(d);
     }
   }
@@ -549,6 +555,93 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
 }
 
 // ------------------------------------------------------------------------------------------
+// Optimizer step / undo fused with the digest of the new state.
+int fused_prepare(Plan &plan) {
+  std::lock_guard<std::mutex> lock(plan.lamb_mu);
+  if (plan.fused_spans) return SWIFT_OK;
+  std::vector<TensorSpan> spans(plan.t_numel.size());
+  for (size_t i = 0; i < spans.size(); ++i) {
+    spans[i].first_slot = plan.t_first_chunk[i];
+    spans[i].n_slots = (plan.t_numel[i] + plan.chunk_elems - 1) / plan.chunk_elems;
+    spans[i].active = plan.t_active[i];
+    spans[i].pad = 0;
+  }
+  void *dspans = nullptr, *dslots = nullptr;
+  SWIFT_HIP(hipMalloc(&dspans, std::max<size_t>(spans.size(), 1) * sizeof(TensorSpan)));
+  hipError_t e = hipMemcpy(dspans, spans.data(), spans.size() * sizeof(TensorSpan), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMalloc(&dslots, std::max<size_t>(plan.n_chunks, 1) * 3 * sizeof(uint64_t));
+  if (e != hipSuccess) {
+    (void)hipFree(dspans);
+    return fail(SWIFT_EHIP, "digest scratch allocation failed: %s", hipGetErrorName(e));
+  }
+  plan.fused_slots = dslots;
+  plan.fused_spans = dspans;
+  return SWIFT_OK;
+}
+
+typedef void (*FusedKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts, unsigned long long *);
+
+FusedKernel pick_fused(int kind, bool undo, bool bf16) {
+#define SWIFT_PICK(K)                                                                                       \
+  (undo ? (bf16 ? opt_digest_kernel<K, true, true, 1, 64> : opt_digest_kernel<K, true, false, 1, 64>)       \
+        : (bf16 ? opt_digest_kernel<K, false, true, 1, 64> : opt_digest_kernel<K, false, false, 1, 64>))
+  switch (kind) {
+    case SWIFT_SGDM: return SWIFT_PICK(kSGDM);
+    case SWIFT_ADAM: return SWIFT_PICK(kADAM);
+    default: return SWIFT_PICK(kADAMW);
+  }
+#undef SWIFT_PICK
+}
+
+int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, uint64_t *digests,
+               bool undo, void *stream_) {
+  OptConsts c;
+  int rc = validate_hparams(hp, undo, &c);
+  if (rc) return rc;
+  if (hp->kind == SWIFT_LAMB) return fail(SWIFT_EINVAL, "the fused digest entry points do not take LAMB");
+  if ((rc = validate_list(l, hp))) return rc;
+  if (l->n == 0) return SWIFT_OK;
+  for (int64_t i = 0; i < l->n; ++i)
+    if (l->numel[i] >= (int64_t)1 << 32)
+      return fail(SWIFT_EINVAL, "tensor %lld has 2^32 elements or more: its digest index would not fit", (long long)i);
+  if (!digests) return fail(SWIFT_EINVAL, "digests_device is NULL");
+  if ((uintptr_t)digests & 7) return fail(SWIFT_EINVAL, "digests_device is not 8-byte aligned");
+  const uint32_t n_groups = hp->kind == SWIFT_SGDM ? 2 : 3;
+  int dev = -1;
+  SWIFT_HIP(hipGetDevice(&dev));
+  DeviceInfo info;
+  if ((rc = device_info(dev, &info))) return rc;
+  if ((rc = check_device_range(digests, (size_t)l->n * n_groups * 8, dev, "digests_device", 0))) return rc;
+  const bool bf16 = hp->grad_dtype == SWIFT_BF16;
+  std::shared_ptr<Plan> plan;
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
+  if ((rc = fused_prepare(*plan))) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Tuning tune = opt_tuning(hp->kind, bf16);
+  tune.u = 1;
+  tune.block = 64;
+  // the digest arithmetic makes this kernel ALU-heavy: more resident wavefronts overlap it with memory
+  tune.waves_per_cu = (int)env_long("SWIFT_FUSED_WAVES_PER_CU", SWIFT_FUSED_WAVES_PER_CU);
+  unsigned long long *slots = static_cast<unsigned long long *>(plan->fused_slots);
+  if (plan->n_chunks) {
+    const uint64_t n_fill = (uint64_t)plan->n_chunks * 3;
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((uint32_t)std::min<uint64_t>((n_fill + kThreads - 1) / kThreads, 4096)),
+                       dim3(kThreads), 0, stream, reinterpret_cast<uint64_t *>(slots), n_fill, (uint64_t)0);
+    SWIFT_HIP(hipGetLastError());
+    const uint32_t shift = shift_for(256u, plan->chunk_elems);
+    const uint64_t n_slots = (uint64_t)plan->n_chunks << shift;
+    hipLaunchKernelGGL(pick_fused(hp->kind, undo, bf16), dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)),
+                       dim3(64), lds_cap_bytes(info, tune), stream, static_cast<const ChunkDesc *>(plan->chunks()),
+                       n_slots, shift, c, slots);
+    SWIFT_HIP(hipGetLastError());
+  }
+  hipLaunchKernelGGL(digest_gather_kernel, dim3((uint32_t)l->n), dim3(64), 0, stream,
+                     static_cast<const TensorSpan *>(plan->fused_spans), slots, (uint32_t)l->n, n_groups, digests);
+  SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // Digest.
 int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, bool set_error) {
   if (n_buf < 0 || (n_buf > 0 && !numel) || shard_elems < 0 || shard_elems >= (int64_t)1 << 32)
@@ -662,6 +755,16 @@ int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
                          void *hip_stream) {
   return opt_call(list, hp, nullptr, device_mask, true, true, hip_stream);
+}
+
+int swift_opt_step_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                          uint64_t *digests_device, void *hip_stream) {
+  return fused_call(list, hp, host_mask, digests_device, false, hip_stream);
+}
+
+int swift_opt_undo_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
+                          uint64_t *digests_device, void *hip_stream) {
+  return fused_call(list, hp, host_mask, digests_device, true, hip_stream);
 }
 
 int swift_lamb_step(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,

@@ -50,7 +50,7 @@ struct LambMomentsOp {
   static constexpr bool kLoadG = true, kHasV = true, kStoreX = false, kStoreM = true, kStoreV = true;
   const OptConsts &c;
   double sx = 0.0, su = 0.0;
-  __device__ __forceinline__ void elem(float &xf, float gf, float &mf, float &vf) {
+  __device__ __forceinline__ void elem(uint32_t, float &xf, float gf, float &mf, float &vf) {
     const double x = (double)xf, g = (double)gf;
     const double mt = fma(c.b1, (double)mf, c.c1 * g);
     const double vt = fma(c.b2, (double)vf, c.c2 * (g * g));
@@ -68,7 +68,7 @@ struct LambApplyOp {
   static constexpr bool kLoadG = false, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false;
   const OptConsts &c;
   double eta_q;
-  __device__ __forceinline__ void elem(float &xf, float, float &mf, float &vf) {
+  __device__ __forceinline__ void elem(uint32_t, float &xf, float, float &mf, float &vf) {
     const double x = (double)xf;
     const double r = ((double)mf * c.rbc1) / (sqrt((double)vf * c.rbc2) + c.eps);
     xf = (float)fma(-eta_q, fma(c.lam, x, r), x);

@@ -28,6 +28,7 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #define SWIFT_DEFAULT_WAVES_PER_CU 11
 #define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
 #define SWIFT_DEFAULT_GROUP_SHIFT_DMASK 0
+#define SWIFT_FUSED_WAVES_PER_CU 24     // step/undo fused with the digest
 #define SWIFT_LAMB_WAVES_P1 6           // LAMB pass 1 (U = 4): wavefronts per CU
 #define SWIFT_LAMB_WAVES_P3 24          // LAMB pass 3 (3 streams in, 1 out)
 #define SWIFT_DEFAULT_DMASK_WGS_PER_CU 16384
@@ -48,7 +49,7 @@ struct ChunkDesc {         // one per chunk of the optimizer kernels, 48 bytes, 
   uint32_t len;            // elements in this chunk (the last chunk of a tensor is short)
   uint32_t tensor;         // index of the tensor in the caller's list (for the device mask)
   uint32_t vec_ok;         // 1: all four pointers are aligned for the 128-bit path
-  uint32_t pad;
+  uint32_t elem0;          // index of the chunk's first element inside its tensor (mod 2^32)
 };
 
 struct ChunkRef {          // digest kernel: one per chunk, 8 bytes, device resident
@@ -153,21 +154,24 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
 // An "op" tells process_tile which streams a kernel moves and what to do with one element:
 //   kLoadG, kHasV          gradient / second moment are read
 //   kStoreX, kStoreM, kStoreV   streams written back
-//   elem(x, g, m, v)       the element arithmetic (may also accumulate into members of the op)
+//   elem(i, x, g, m, v)    the arithmetic of element i of the chunk (may also accumulate into
+//                          members of the op)
 template <int KIND, bool UNDO>
 struct OptOp {             // optimizer step or undo of one element
   static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
   static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV;
   const OptConsts &c;
-  __device__ __forceinline__ void elem(float &x, float g, float &m, float &v) { update_elem<KIND, UNDO>(x, g, m, v, c); }
+  __device__ __forceinline__ void elem(uint32_t, float &x, float g, float &m, float &v) {
+    update_elem<KIND, UNDO>(x, g, m, v, c);
+  }
 };
 
 template <typename Op>
-__device__ __forceinline__ void update_vec4(Op &op, f32x4 &x, const f32x4 &g, f32x4 &m, f32x4 &v) {
+__device__ __forceinline__ void update_vec4(Op &op, uint32_t j, f32x4 &x, const f32x4 &g, f32x4 &m, f32x4 &v) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     float xe = x[k], me = m[k], ve = Op::kHasV ? v[k] : 0.f;
-    op.elem(xe, Op::kLoadG ? g[k] : 0.f, me, ve);
+    op.elem(4u * j + k, xe, Op::kLoadG ? g[k] : 0.f, me, ve);
     x[k] = xe;
     m[k] = me;
     if constexpr (Op::kHasV) v[k] = ve;
@@ -202,7 +206,7 @@ __device__ __forceinline__ void process_scalar(Op &op, const ChunkDesc &d, uint3
   float xe = ld<false>(d.x + e), me = ld<false>(d.m + e), ve = 0.f, ge = 0.f;
   if constexpr (Op::kHasV) ve = ld<false>(d.v + e);
   if constexpr (Op::kLoadG) ge = load_grad1<BF16G>(d.g, e);
-  op.elem(xe, ge, me, ve);
+  op.elem(e, xe, ge, me, ve);
   if constexpr (Op::kStoreX) st<false>(d.x + e, xe);
   if constexpr (Op::kStoreM) st<false>(d.m + e, me);
   if constexpr (Op::kStoreV) st<false>(d.v + e, ve);
@@ -235,7 +239,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t j = j0 + u * BLOCK + tid;
-        update_vec4(op, xr[u], gr[u], mr[u], vr[u]);
+        update_vec4(op, j, xr[u], gr[u], mr[u], vr[u]);
         if constexpr (Op::kStoreX) buf_st4(rx, j * 16u, xr[u]);
         if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr[u]);
         if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr[u]);
@@ -245,7 +249,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
         f32x4 xr = buf_ld4(rx, j * 16u), mr = buf_ld4(rm, j * 16u);
         f32x4 gr = Op::kLoadG ? load_grad4<BF16G>(rg, j) : f32x4{0.f, 0.f, 0.f, 0.f};
         f32x4 vr = HASV ? buf_ld4(rv, j * 16u) : f32x4{0.f, 0.f, 0.f, 0.f};
-        update_vec4(op, xr, gr, mr, vr);
+        update_vec4(op, j, xr, gr, mr, vr);
         if constexpr (Op::kStoreX) buf_st4(rx, j * 16u, xr);
         if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr);
         if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr);
