@@ -179,6 +179,36 @@ int64_t swift_digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_el
 int swift_mask_from_digests(int64_t n_tensors, int64_t n_groups, const uint64_t *before_device,
                             const uint64_t *after_device, uint8_t *mask_device, void *hip_stream);
 
+/* Update tracker: the paper's own bookkeeping (Implementation, "Update-undo").  In data-parallel
+ * training the update of a tensor is launched as soon as its gradient is final (after that tensor's
+ * all-reduce), and the tensor is then marked as updated; after a failure the survivors let the kernels
+ * already launched finish and undo exactly the marked tensors.  The tracker is host state plus one event
+ * per tracked launch; ids refer to the positions of the tensors in the caller's full list.
+ *   swift_tracker_create   n_tensors >= 0; *out receives the handle (HOST, owned by the library).
+ *   swift_tracker_begin    starts iteration `step` (>= 1) and drops the marks of the previous one.
+ *   swift_tracker_step     `group` is a sub-list of the full list, tensor_ids[k] (HOST, group->n entries)
+ *                          the position of group tensor k in the full list.  If grad_ready_event (a
+ *                          hipEvent_t, nullable) is given, the stream waits for it first; then
+ *                          swift_opt_step(group, hp, NULL, stream) is enqueued and the ids are marked.
+ *                          hp->step must equal the iteration in progress; an id already marked in this
+ *                          iteration is an error (SWIFT_EINVAL) and nothing is enqueued.
+ *   swift_tracker_marks    waits until every tracked launch of this iteration has finished, then copies
+ *                          the marks (HOST, n_tensors bytes, 1 = updated).
+ *   swift_tracker_undo     the same wait, then swift_opt_undo(list, hp, marks, stream) on the FULL list
+ *                          (list->n must equal n_tensors) and the marks are cleared: the replica is back
+ *                          at the start of the iteration.
+ *   swift_tracker_destroy  waits for tracked launches, frees the handle (NULL is allowed).
+ * One tracker serves one GPU and one training loop; its calls are serialised by an internal lock. */
+typedef struct swift_tracker swift_tracker;
+int swift_tracker_create(int64_t n_tensors, swift_tracker **out);
+int swift_tracker_begin(swift_tracker *tracker, int64_t step);
+int swift_tracker_step(swift_tracker *tracker, const swift_tensor_list *group, const int64_t *tensor_ids,
+                       const swift_hparams *hp, void *grad_ready_event, void *hip_stream);
+int swift_tracker_marks(swift_tracker *tracker, uint8_t *host_mask_out);
+int swift_tracker_undo(swift_tracker *tracker, const swift_tensor_list *list, const swift_hparams *hp,
+                       void *hip_stream);
+int swift_tracker_destroy(swift_tracker *tracker);
+
 /* Measurement aid: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers
  * 16-byte aligned, DEVICE) written with the same access pattern as the optimizer kernels.  It
  * gives the practical HBM ceiling of this access pattern and calibrates profiler byte counters. */

@@ -56,6 +56,15 @@ _lib.swift_mask_from_digests.argtypes = [ctypes.c_int64, ctypes.c_int64, _P, _P,
 _lib.swift_mask_from_digests.restype = ctypes.c_int
 _lib.swift_stream_copy.argtypes = [_P, _P, ctypes.c_int64, _P]
 _lib.swift_stream_copy.restype = ctypes.c_int
+_lib.swift_tracker_create.argtypes = [ctypes.c_int64, ctypes.POINTER(_P)]
+_lib.swift_tracker_begin.argtypes = [_P, ctypes.c_int64]
+_lib.swift_tracker_step.argtypes = [_P, ctypes.POINTER(SwiftTensorList), ctypes.POINTER(ctypes.c_int64),
+                                    ctypes.POINTER(SwiftHparams), _P, _P]
+_lib.swift_tracker_marks.argtypes = [_P, _P]
+_lib.swift_tracker_undo.argtypes = [_P, ctypes.POINTER(SwiftTensorList), ctypes.POINTER(SwiftHparams), _P]
+_lib.swift_tracker_destroy.argtypes = [_P]
+for _name in ("create", "begin", "step", "marks", "undo", "destroy"):
+    getattr(_lib, "swift_tracker_" + _name).restype = ctypes.c_int
 _lib.swift_shutdown.argtypes = []
 _lib.swift_shutdown.restype = ctypes.c_int
 _lib.swift_last_error.argtypes = []
@@ -63,6 +72,8 @@ _lib.swift_last_error.restype = ctypes.c_char_p
 
 EXPORTS = ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask",
            "swift_lamb_step", "swift_lamb_undo", "swift_opt_step_digest", "swift_opt_undo_digest",
+           "swift_tracker_create", "swift_tracker_begin", "swift_tracker_step", "swift_tracker_marks",
+           "swift_tracker_undo", "swift_tracker_destroy",
            "swift_state_digest", "swift_digest_count", "swift_mask_from_digests", "swift_stream_copy",
            "swift_shutdown", "swift_last_error")
 
@@ -277,6 +288,47 @@ def swift_mask_from_digests(before: torch.Tensor, after: torch.Tensor, n_tensors
                                         after.data_ptr() if n_tensors else None,
                                         out.data_ptr() if n_tensors else None, _stream_handle(stream)))
     return out
+
+
+class Tracker:
+    """swift_tracker_*: the paper's per-parameter "marked as updated" bookkeeping for one training loop."""
+
+    def __init__(self, n_tensors: int):
+        self._h = ctypes.c_void_p()
+        _check(_lib.swift_tracker_create(int(n_tensors), ctypes.byref(self._h)))
+        self.n = int(n_tensors)
+
+    def begin(self, step: int) -> None:
+        _check(_lib.swift_tracker_begin(self._h, int(step)))
+
+    def step(self, group: TensorList, tensor_ids: Sequence[int], hp: SwiftHparams, grad_ready_event=None,
+             stream=None) -> None:
+        if len(tensor_ids) != group.n:
+            raise ValueError("one id per tensor of the group")
+        ids = (ctypes.c_int64 * max(group.n, 1))(*tensor_ids)
+        ev = None
+        if grad_ready_event is not None:
+            ev = grad_ready_event.cuda_event if isinstance(grad_ready_event, torch.cuda.Event) else int(grad_ready_event)
+        _check(_lib.swift_tracker_step(self._h, ctypes.byref(group.c), ids, ctypes.byref(hp), ev, _stream_handle(stream)))
+
+    def marks(self) -> List[int]:
+        buf = (ctypes.c_uint8 * max(self.n, 1))()
+        _check(_lib.swift_tracker_marks(self._h, ctypes.cast(buf, _P)))
+        return list(buf[:self.n])
+
+    def undo(self, full: TensorList, hp: SwiftHparams, stream=None) -> None:
+        _check(_lib.swift_tracker_undo(self._h, ctypes.byref(full.c), ctypes.byref(hp), _stream_handle(stream)))
+
+    def close(self) -> None:
+        if self._h:
+            _check(_lib.swift_tracker_destroy(self._h))
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def swift_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

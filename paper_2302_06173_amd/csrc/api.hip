@@ -12,6 +12,7 @@
 #include <list>
 #include <memory>
 #include <mutex>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -114,7 +115,7 @@ struct Plan {
   }
 };
 
-constexpr size_t kMaxPlans = 32;
+constexpr size_t kMaxPlans = 256;   // a layer-wise training loop keeps one plan per layer
 std::mutex g_plan_mu;
 std::list<std::shared_ptr<Plan>> *g_plans = nullptr;   // most recently used first; leaked at exit on purpose
 
@@ -732,6 +733,31 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   return SWIFT_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// Update tracker: the paper's own bookkeeping (Implementation, "Update-undo").  Per iteration the
+// training loop updates tensors group by group as their gradients become final; every tensor
+// whose update kernels have been launched is marked, and after a failure exactly the marked
+// tensors are undone -- once the kernels already launched have run to completion.
+struct Tracker {
+  int64_t n_tensors = 0;
+  int64_t step = 0;                    // iteration whose update is in progress (0: none)
+  int device = -1;
+  std::vector<uint8_t> marks;
+  std::vector<hipEvent_t> pending;     // one per tracked launch of this iteration
+  std::vector<hipEvent_t> pool;        // recycled events
+  std::mutex mu;
+};
+
+int tracker_wait(Tracker &t) {
+  for (hipEvent_t e : t.pending) SWIFT_HIP(hipEventSynchronize(e));
+  return SWIFT_OK;
+}
+
+void tracker_recycle(Tracker &t) {
+  t.pool.insert(t.pool.end(), t.pending.begin(), t.pending.end());
+  t.pending.clear();
+}
+
 }  // namespace
 }  // namespace swift
 
@@ -858,6 +884,135 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
                      static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
                      static_cast<const u32x4 *>(src_device), n16);
   SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+struct swift_tracker {
+  Tracker t;
+};
+
+int swift_tracker_create(int64_t n_tensors, swift_tracker **out) {
+  if (!out) return fail(SWIFT_EINVAL, "tracker: out is NULL");
+  *out = nullptr;
+  if (n_tensors < 0 || n_tensors > (int64_t)0x7fffffff) return fail(SWIFT_EINVAL, "tracker: tensor count out of range");
+  swift_tracker *tr = new (std::nothrow) swift_tracker();
+  if (!tr) return fail(SWIFT_EHIP, "tracker: out of host memory");
+  tr->t.n_tensors = n_tensors;
+  tr->t.marks.assign((size_t)n_tensors, 0);
+  *out = tr;
+  return SWIFT_OK;
+}
+
+int swift_tracker_destroy(swift_tracker *tr) {
+  if (!tr) return SWIFT_OK;
+  Tracker &t = tr->t;
+  int rc = SWIFT_OK;
+  {
+    std::lock_guard<std::mutex> lock(t.mu);
+    rc = tracker_wait(t);              // launched kernels finish before their events go away
+    tracker_recycle(t);
+    for (hipEvent_t e : t.pool) (void)hipEventDestroy(e);
+    t.pool.clear();
+  }
+  delete tr;
+  return rc;
+}
+
+int swift_tracker_begin(swift_tracker *tr, int64_t step) {
+  if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
+  if (step < 1) return fail(SWIFT_EINVAL, "tracker: step must be >= 1");
+  Tracker &t = tr->t;
+  std::lock_guard<std::mutex> lock(t.mu);
+  // the previous iteration's update is complete on every replica once the next one begins (the
+  // paper's argument for keeping a single gradient version): its marks are dropped
+  tracker_recycle(t);
+  std::fill(t.marks.begin(), t.marks.end(), 0);
+  t.step = step;
+  return SWIFT_OK;
+}
+
+int swift_tracker_step(swift_tracker *tr, const swift_tensor_list *group, const int64_t *tensor_ids,
+                       const swift_hparams *hp, void *grad_ready_event, void *hip_stream) {
+  if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
+  if (!group || !hp) return fail(SWIFT_EINVAL, "tracker: group or hparams is NULL");
+  if (group->n > 0 && !tensor_ids) return fail(SWIFT_EINVAL, "tracker: tensor_ids is NULL");
+  Tracker &t = tr->t;
+  std::lock_guard<std::mutex> lock(t.mu);
+  if (t.step == 0) return fail(SWIFT_EINVAL, "tracker: swift_tracker_begin has not been called");
+  if (hp->step != t.step)
+    return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
+                (long long)t.step);
+  for (int64_t k = 0; k < group->n; ++k) {
+    const int64_t id = tensor_ids[k];
+    if (id < 0 || id >= t.n_tensors) return fail(SWIFT_EINVAL, "tracker: tensor id %lld out of range", (long long)id);
+    if (t.marks[(size_t)id]) return fail(SWIFT_EINVAL, "tracker: tensor %lld was already updated in this iteration", (long long)id);
+    for (int64_t j = 0; j < k; ++j)
+      if (tensor_ids[j] == id) return fail(SWIFT_EINVAL, "tracker: tensor id %lld appears twice", (long long)id);
+  }
+  int dev = -1;
+  SWIFT_HIP(hipGetDevice(&dev));
+  if (t.device < 0) t.device = dev;
+  if (dev != t.device) return fail(SWIFT_EINVAL, "tracker: created for device %d, current device is %d", t.device, dev);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipEvent_t done;
+  if (!t.pool.empty()) {
+    done = t.pool.back();
+    t.pool.pop_back();
+  } else {
+    SWIFT_HIP(hipEventCreateWithFlags(&done, hipEventDisableTiming));
+  }
+  // the update waits (on the device) for the gradient to be final, as the paper's loop waits for the
+  // all-reduce of that tensor before launching its update kernels
+  if (grad_ready_event) {
+    hipError_t e = hipStreamWaitEvent(stream, static_cast<hipEvent_t>(grad_ready_event), 0);
+    if (e != hipSuccess) {
+      t.pool.push_back(done);
+      return fail(SWIFT_EHIP, "hipStreamWaitEvent failed: %s", hipGetErrorName(e));
+    }
+  }
+  const int rc = swift_opt_step(group, hp, nullptr, hip_stream);
+  if (rc != SWIFT_OK) {
+    t.pool.push_back(done);
+    return rc;                         // nothing was launched, nothing is marked
+  }
+  hipError_t e = hipEventRecord(done, stream);
+  if (e != hipSuccess) {
+    // the kernels are in flight but cannot be tracked by an event: wait for them here, then mark
+    (void)hipStreamSynchronize(stream);
+    t.pool.push_back(done);
+  } else {
+    t.pending.push_back(done);
+  }
+  for (int64_t k = 0; k < group->n; ++k) t.marks[(size_t)tensor_ids[k]] = 1;
+  return SWIFT_OK;
+}
+
+int swift_tracker_marks(swift_tracker *tr, uint8_t *host_mask_out) {
+  if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
+  if (!host_mask_out && tr->t.n_tensors > 0) return fail(SWIFT_EINVAL, "tracker: host_mask_out is NULL");
+  Tracker &t = tr->t;
+  std::lock_guard<std::mutex> lock(t.mu);
+  int rc = tracker_wait(t);            // "we need to let these kernels finish executing"
+  if (rc) return rc;
+  if (t.n_tensors) memcpy(host_mask_out, t.marks.data(), (size_t)t.n_tensors);
+  return SWIFT_OK;
+}
+
+int swift_tracker_undo(swift_tracker *tr, const swift_tensor_list *list, const swift_hparams *hp, void *hip_stream) {
+  if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
+  if (!list || !hp) return fail(SWIFT_EINVAL, "tracker: list or hparams is NULL");
+  Tracker &t = tr->t;
+  std::lock_guard<std::mutex> lock(t.mu);
+  if (list->n != t.n_tensors) return fail(SWIFT_EINVAL, "tracker: the list has %lld tensors, the tracker %lld", (long long)list->n, (long long)t.n_tensors);
+  if (t.step == 0 || hp->step != t.step)
+    return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
+                (long long)t.step);
+  int rc = tracker_wait(t);
+  if (rc) return rc;
+  rc = swift_opt_undo(list, hp, t.marks.data(), hip_stream);
+  if (rc) return rc;
+  tracker_recycle(t);
+  std::fill(t.marks.begin(), t.marks.end(), 0);   // the state is back at the start of the iteration
   return SWIFT_OK;
 }
 

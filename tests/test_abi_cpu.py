@@ -149,3 +149,34 @@ def test_synthetic_workloads_have_the_stated_sizes():
     assert s1.v is None
     mask = synth.tensor_mask(w["llama7b_adamw"], 291)
     assert sum(mask) == 146 and mask == synth.tensor_mask(w["llama7b_adamw"], 291)
+
+
+def test_tracker_host_logic_without_a_gpu(B):
+    h = ctypes.c_void_p()
+    assert B._lib.swift_tracker_create(-1, ctypes.byref(h)) == B.SWIFT_EINVAL
+    assert B._lib.swift_tracker_create(3, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_tracker_create(3, ctypes.byref(h)) == B.SWIFT_OK and h.value
+    hp = B.hparams("adamw", step=5, lr=1e-3)
+    lst = B.SwiftTensorList(0, None, None, None, None, None)
+    ids = (ctypes.c_int64 * 1)(0)
+    # no iteration in progress yet
+    assert B._lib.swift_tracker_step(h, ctypes.byref(lst), ids, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "begin" in B.swift_last_error()
+    assert B._lib.swift_tracker_begin(h, 0) == B.SWIFT_EINVAL
+    assert B._lib.swift_tracker_begin(h, 4) == B.SWIFT_OK
+    # the step of the hyper-parameters must be the iteration in progress
+    assert B._lib.swift_tracker_step(h, ctypes.byref(lst), ids, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_tracker_step(h, None, ids, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_tracker_begin(h, 5) == B.SWIFT_OK
+    one = B.SwiftTensorList(1, None, None, None, None, None)
+    bad = (ctypes.c_int64 * 1)(7)
+    assert B._lib.swift_tracker_step(h, ctypes.byref(one), bad, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "out of range" in B.swift_last_error()
+    assert B._lib.swift_tracker_step(h, ctypes.byref(one), None, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    marks = (ctypes.c_uint8 * 3)(9, 9, 9)
+    assert B._lib.swift_tracker_marks(h, ctypes.cast(marks, ctypes.c_void_p)) == B.SWIFT_OK    # nothing pending
+    assert list(marks) == [0, 0, 0]
+    assert B._lib.swift_tracker_marks(h, None) == B.SWIFT_EINVAL
+    assert B._lib.swift_tracker_undo(h, ctypes.byref(one), ctypes.byref(hp), None) == B.SWIFT_EINVAL   # wrong length
+    assert B._lib.swift_tracker_destroy(h) == B.SWIFT_OK
+    assert B._lib.swift_tracker_destroy(None) == B.SWIFT_OK

@@ -1,0 +1,115 @@
+"""The update tracker (paper, Implementation, "Update-undo"): tensors are updated group by group as
+their gradients become final and marked; after a failure exactly the marked tensors are undone."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_parity, binding_hparams, digests_np, oracle_hyper, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2302_06173_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def synth():
+    from paper_2302_06173_amd import synth
+    return synth
+
+
+def _groups(n_tensors, per_group):
+    ids = list(range(n_tensors))
+    return [ids[k:k + per_group] for k in range(0, n_tensors, per_group)]
+
+
+def test_layerwise_update_failure_and_undo(B, synth):
+    """BERT-large list, updated in reverse layer order (gradients arrive from the last layer first, as in the
+    paper's figure); the 'failure' strikes after 9 of 25 groups."""
+    w = synth.workloads()["bert_large_adamw"]
+    s = synth.make_state(w, "cuda")
+    n = len(w.shapes)
+    hpd = dict(w.hyper, step=3)
+    hp = binding_hparams(B, w.kind, hpd)
+    full = B.TensorList(s.theta, s.grad, s.m, s.v)
+    groups = list(reversed(_groups(n, 16)))
+    lists = [B.TensorList([s.theta[i] for i in g], [s.grad[i] for i in g], [s.m[i] for i in g], [s.v[i] for i in g])
+             for g in groups]
+    bufs = B.BufferList(s.theta + s.m + s.v)
+    tr = B.Tracker(n)
+    # iteration 2 completes normally: every group stepped, marks all set, then the next begin clears them
+    tr.begin(2)
+    hp2 = binding_hparams(B, w.kind, dict(w.hyper, step=2))
+    for g, tl in zip(groups, lists):
+        tr.step(tl, g, hp2)
+    assert tr.marks() == [1] * n
+    # iteration 3: digests of the consistent state, then the update is interrupted
+    tr.begin(3)
+    assert tr.marks() == [0] * n
+    d0 = B.swift_state_digest(bufs, 0)
+    picks = [groups[0][0], groups[3][5], groups[8][15], groups[9][0], groups[-1][-1], 0]
+    pre = {i: tuple(to_np(t[i]) for t in (s.theta, s.grad, s.m, s.v)) for i in picks}
+    side = torch.cuda.Stream()
+    ready = torch.cuda.Event()
+    for k, (g, tl) in enumerate(zip(groups, lists)):
+        if k == 9:
+            break                                               # the failure is noticed here
+        ready.record()                                          # stands for "all-reduce of this group done"
+        tr.step(tl, g, hp, grad_ready_event=ready, stream=side)
+    with pytest.raises(B.SwiftError) as e:                      # a tensor cannot be updated twice in one iteration
+        tr.step(lists[2], groups[2], hp, stream=side)
+    assert e.value.code == B.SWIFT_EINVAL
+    with pytest.raises(B.SwiftError):                           # nor with another iteration's hyper-parameters
+        tr.step(lists[10], groups[10], hp2, stream=side)
+    marks = tr.marks()                                          # waits for the launched kernels
+    want = [0] * n
+    for g in groups[:9]:
+        for i in g:
+            want[i] = 1
+    assert marks == want
+    # the digest-derived mask (memory contents only) agrees with the tracker's marks
+    d1 = B.swift_state_digest(bufs, 0)
+    dmask = B.swift_mask_from_digests(d0, d1, n)
+    torch.cuda.synchronize()
+    assert dmask.cpu().tolist() == want
+    mid = {i: tuple(to_np(t[i]) for t in (s.theta, s.grad, s.m, s.v)) for i in picks}
+    h = oracle_hyper(w.kind, hpd)
+    for i in picks:
+        x, g_, m, v = pre[i]
+        if want[i]:
+            rx, rm, rv = oracle.opt_step(h, x, g_, m, v)
+            sc = float(max(np.abs(a).max() for a in (x, g_, m, v)))
+            assert_parity(mid[i][0], rx, f"tracked step theta[{i}]", sc)
+            assert_parity(mid[i][2], rm, f"tracked step m[{i}]", sc)
+            assert_parity(mid[i][3], rv, f"tracked step v[{i}]", sc)
+        else:
+            for k in (0, 2, 3):
+                assert np.array_equal(pre[i][k].view(np.uint32), mid[i][k].view(np.uint32))
+    tr.undo(full, hp)
+    d2 = B.swift_state_digest(bufs, 0)
+    torch.cuda.synchronize()
+    assert tr.marks() == [0] * n
+    a, c = digests_np(d0).reshape(3, n), digests_np(d2).reshape(3, n)
+    off = ~np.array(want, bool)
+    assert np.array_equal(a[:, off], c[:, off])                 # never-updated tensors kept their bits
+    end = {i: tuple(to_np(t[i]) for t in (s.theta, s.grad, s.m, s.v)) for i in picks}
+    for i in picks:
+        if want[i]:
+            x, g_, m, v = mid[i]
+            rx, rm, rv = oracle.opt_undo(h, x, g_, m, v)
+            sc = float(max(np.abs(a_).max() for a_ in (x, g_, m, v)))
+            assert_parity(end[i][0], rx, f"tracked undo theta[{i}]", sc)
+            assert_parity(end[i][2], rm, f"tracked undo m[{i}]", sc)
+            assert_parity(end[i][3], rv, f"tracked undo v[{i}]", sc * max(sc, 1.0))
+    # training resumes at iteration 3 with the same tracker
+    tr.begin(3)
+    for g, tl in zip(groups, lists):
+        tr.step(tl, g, hp)
+    assert tr.marks() == [1] * n
+    with pytest.raises(B.SwiftError):                           # the full list must match the tracker
+        tr.undo(lists[0], hp)
+    tr.close()
