@@ -396,7 +396,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   return SWIFT_OK;
 }
 
-typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, uint32_t, const uint8_t *, const OptConsts);
+typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const uint8_t *, const OptConsts);
 
 template <int U, int BLOCK>
 OptKernel pick_kernel_shape(int kind, bool undo, bool bf16) {
@@ -443,12 +443,7 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   if (plan->n_chunks == 0) return SWIFT_OK;
   uint32_t tpc_shift = 0;
   while ((tile_elems << tpc_shift) < plan->chunk_elems) ++tpc_shift;
-  // Tiles per workgroup: one, except with a device mask, where skipped tensors still cost a
-  // dispatch per group, so groups are larger (both can be overridden for sweeps).
-  uint32_t grp_shift = (uint32_t)env_long(want_dmask ? "SWIFT_GROUP_SHIFT_DMASK" : "SWIFT_GROUP_SHIFT",
-                                          want_dmask ? SWIFT_DEFAULT_GROUP_SHIFT_DMASK : 0);
-  if (grp_shift > tpc_shift) grp_shift = tpc_shift;
-  const uint64_t n_groups = ((uint64_t)plan->n_chunks << tpc_shift) >> grp_shift;
+  const uint64_t n_slots = (uint64_t)plan->n_chunks << tpc_shift;
   uint64_t grid_cap = 0x7fffffffull;
   if (want_dmask) {
     // With a device mask the host cannot size the grid to the marked tensors, and every skipped
@@ -460,10 +455,10 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
     const long per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
     if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
   }
-  const uint32_t grid = (uint32_t)std::min<uint64_t>(n_groups, grid_cap);
+  const uint32_t grid = (uint32_t)std::min<uint64_t>(n_slots, grid_cap);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3((uint32_t)tune.block), lds_cap_bytes(info, tune),
-                     static_cast<hipStream_t>(stream), static_cast<const ChunkDesc *>(plan->chunks()), n_groups,
-                     tpc_shift, grp_shift, device_mask, c);
+                     static_cast<hipStream_t>(stream), static_cast<const ChunkDesc *>(plan->chunks()), n_slots,
+                     tpc_shift, device_mask, c);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }

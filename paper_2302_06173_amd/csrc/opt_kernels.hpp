@@ -27,7 +27,6 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #define SWIFT_DEFAULT_BLOCK 64
 #define SWIFT_DEFAULT_WAVES_PER_CU 11
 #define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
-#define SWIFT_DEFAULT_GROUP_SHIFT_DMASK 0
 #define SWIFT_FUSED_WAVES_PER_CU 24     // step/undo fused with the digest
 #define SWIFT_LAMB_WAVES_P1 6           // LAMB pass 1 (U = 4): wavefronts per CU
 #define SWIFT_LAMB_WAVES_P3 24          // LAMB pass 3 (3 streams in, 1 out)
@@ -275,44 +274,36 @@ __device__ __forceinline__ bool tensor_is_marked(const uint8_t *dmask, uint32_t 
   return ((word >> (8u * (uint32_t)(a & 3u))) & 0xFFu) != 0;
 }
 
-// One workgroup per group of 2^grp_shift consecutive tiles (normally one tile).  A chunk is up to
-// chunk_elems consecutive elements of one tensor (the last chunk of a tensor is short) and spans
-// 2^tpc_shift tile slots, so tile slot w is tile (w & (tpc-1)) of chunk (w >> tpc_shift); groups
-// never straddle chunks (grp_shift <= tpc_shift).  The chunk table holds ready-made pointers, so
-// a wavefront is one scalar load away from issuing its vector loads.  The grid normally equals
-// the number of groups: the hardware dispatcher then hands tiles out in address order as
-// wavefronts retire, which keeps the window of HBM pages in flight narrow (a persistent
-// grid-stride loop lets workgroups drift apart and measured 10-20 % slower for this
-// 4-read/3-write pattern).  The launch passes dynamic LDS that is never touched: it only caps how
-// many workgroups share a compute unit, because more than ~11 wavefronts per CU in flight lowers
-// the achieved HBM bandwidth of the mixed read/write stream.
-// `dmask` (nullable) holds one byte per tensor in device memory: groups of tensors whose byte
-// is zero are skipped (such launches use larger groups, so that skipping costs fewer dispatches).
+// One workgroup per tile.  A chunk is up to chunk_elems consecutive elements of one tensor (the last
+// chunk of a tensor is short) and spans 2^tpc_shift tile slots, so slot w is tile (w & (tpc-1)) of
+// chunk (w >> tpc_shift).  The chunk table holds ready-made pointers, so a wavefront is one round
+// of scalar loads away from issuing its vector loads.  The grid normally equals the number of
+// slots: the hardware dispatcher then hands tiles out in address order as wavefronts retire, which
+// keeps the window of HBM pages in flight narrow (a persistent grid-stride loop lets workgroups
+// drift apart and measured 10-20 % slower for this 4-read/3-write pattern; so did several tiles
+// per workgroup).  The launch passes dynamic LDS that is never touched: it only caps how many
+// workgroups share a compute unit, because more than ~11 wavefronts per CU in flight lowers the
+// achieved HBM bandwidth of the mixed read/write stream.
+// `dmask` (nullable) holds one byte per tensor in device memory: tiles of tensors whose byte is
+// zero are skipped; such launches use a capped grid and stride over the slots.
 template <int KIND, bool UNDO, bool BF16G, int U, int BLOCK>
 __global__ void __launch_bounds__(BLOCK)
-opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_groups, uint32_t tpc_shift, uint32_t grp_shift,
+opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_shift,
            const uint8_t *__restrict__ dmask, const OptConsts c) {
   constexpr uint32_t TILE = U * BLOCK * 4u;                      // elements per tile
-  const uint32_t tid = threadIdx.x;
   OptOp<KIND, UNDO> op{c};
-  // The host launches at most n_groups workgroups, so the first pass needs no bounds test (and no
-  // wait for n_groups before the chunk entry can be fetched).
-  uint64_t grp = blockIdx.x;
+  // The host launches at most n_slots workgroups, so the first pass needs no bounds test (and no
+  // wait for n_slots before the chunk entry can be fetched).
+  uint64_t w = blockIdx.x;
   do {
-    const uint64_t w0 = grp << grp_shift;                        // first tile slot of the group
-    const ChunkDesc d = chunks[w0 >> tpc_shift];
-    const uint32_t ti0 = (uint32_t)w0 & ((1u << tpc_shift) - 1u);
+    const ChunkDesc d = chunks[w >> tpc_shift];
+    const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
     // (the pointer test is always true for a chunk with elements; it makes the compiler fetch the
     //  whole entry with one round of scalar loads instead of the length first and the pointers later)
-    if (ti0 * TILE >= d.len || d.x == nullptr) continue;         // short last chunk: nothing here
+    if (ti * TILE >= d.len || d.x == nullptr) continue;          // slot past the end of a short chunk
     if (dmask != nullptr && !tensor_is_marked(dmask, d.tensor)) continue;
-    const uint32_t n_tiles = 1u << grp_shift;
-    for (uint32_t k = 0; k < n_tiles; ++k) {
-      const uint32_t ti = ti0 + k;
-      if (ti * TILE >= d.len) break;
-      process_tile<OptOp<KIND, UNDO>, BF16G, U, BLOCK>(op, d, ti, tid);
-    }
-  } while ((grp += gridDim.x) < n_groups);
+    process_tile<OptOp<KIND, UNDO>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
+  } while ((w += gridDim.x) < n_slots);
 }
 
 // Plain copy with the same launch shape (one tile of U*BLOCK 16-byte vectors per workgroup): the
