@@ -657,19 +657,22 @@ int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, b
   return total;
 }
 
-// Digest chunks: one workgroup and one 64-bit atomic per chunk.
-// Whole-buffer shards of large tensors get longer chunks: fewer atomics land on one address.
-uint32_t digest_chunk_elems(uint64_t total, int64_t shard_elems) {
+// Digest chunks: one workgroup and one 64-bit atomic per chunk.  Long chunks mean fewer atomics on
+// one address (whole-tensor shards of large tensors), but the launch still needs about sixteen
+// workgroups per compute unit to fill the chip, so the length follows the total size.
+uint32_t digest_chunk_elems(uint64_t total, int64_t shard_elems, int cus) {
   const uint32_t tile = 4u * kThreads * 4;                     // largest unroll the kernel is built with
   long forced = env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0);       // tuning knob for sweeps
   if (forced >= (long)tile && forced <= (1l << 22) && forced % tile == 0) return (uint32_t)forced;
-  if (total < (1ull << 22)) return tile;                       // small: many short chunks fill the chip
-  if (total < (1ull << 26)) return 4u * tile;                  // measured best for a ResNet-50-sized state
-  return shard_elems == 0 ? 4u * SWIFT_DIGEST_CHUNK : SWIFT_DIGEST_CHUNK;
+  const uint32_t cap = shard_elems == 0 ? 4u * SWIFT_DIGEST_CHUNK : SWIFT_DIGEST_CHUNK;
+  const uint64_t want = total / (16ull * (uint64_t)cus);
+  uint32_t ce = tile;
+  while (ce < cap && (uint64_t)ce * 2 <= want) ce *= 2;
+  return ce;
 }
 
 int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *numel, int64_t shard_elems, int dev,
-                      std::shared_ptr<Plan> *out) {
+                      int cus, std::shared_ptr<Plan> *out) {
   std::string key;
   key.reserve(64 + (size_t)n_buf * 16);
   key_add(key, (uint8_t)'D');
@@ -702,7 +705,7 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   plan->key = std::move(key);
   plan->device = dev;
   plan->n_out = n_out;
-  plan->chunk_elems = digest_chunk_elems(total, shard_elems);
+  plan->chunk_elems = digest_chunk_elems(total, shard_elems, cus);
   const uint64_t ce = plan->chunk_elems;
   std::vector<ChunkRef> chunks;
   chunks.reserve((size_t)(total / ce) + (size_t)n_out);
@@ -818,7 +821,7 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
   const long du = env_long("SWIFT_DIGEST_U", SWIFT_DIGEST_U);   // tuning knob for sweeps
   const auto kernel = du == 1 ? digest_kernel<1> : du == 2 ? digest_kernel<2> : digest_kernel<4>;
   std::shared_ptr<Plan> plan;
-  if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, &plan))) return rc;
+  if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, info.cus, &plan))) return rc;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   // The output is cleared by a kernel (not a memset node) so that the call can be captured in a graph.
   const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
