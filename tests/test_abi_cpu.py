@@ -180,3 +180,14 @@ def test_tracker_host_logic_without_a_gpu(B):
     assert B._lib.swift_tracker_undo(h, ctypes.byref(one), ctypes.byref(hp), None) == B.SWIFT_EINVAL   # wrong length
     assert B._lib.swift_tracker_destroy(h) == B.SWIFT_OK
     assert B._lib.swift_tracker_destroy(None) == B.SWIFT_OK
+
+
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C (no C++ or HIP types in the signatures)
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text('#include "swift_undo.h"\n'
+                   'int probe(void) { swift_hparams hp; swift_tensor_list l; hp.kind = SWIFT_LAMB; l.n = 0;\n'
+                   '  return swift_opt_step(&l, &hp, 0, 0) + (int)swift_digest_count(0, 0, 0); }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
