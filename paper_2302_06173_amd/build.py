@@ -12,8 +12,11 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libswift_undo.so")
 SOURCES = [os.path.join(PKG, "csrc", "api.hip")]
-HEADERS = [os.path.join(PKG, "csrc", "opt_kernels.hpp"), os.path.join(PKG, "csrc", "digest_kernels.hpp"),
-           os.path.join(ROOT, "include", "swift_undo.h")]
+HEADERS = [os.path.join(PKG, "csrc", h) for h in
+           ("opt_kernels.hpp", "digest_kernels.hpp", "lamb_kernels.hpp", "fused_kernels.hpp")] + \
+          [os.path.join(ROOT, "include", "swift_undo.h")]
+EXAMPLE_SRC = os.path.join(PKG, "csrc", "example_undo_roundtrip.c")
+EXAMPLE = os.path.join(PKG, "example_undo_roundtrip.bin")
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
@@ -29,7 +32,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS + [EXAMPLE_SRC]) or not os.path.exists(EXAMPLE)
 
 
 def build(force: bool = True, extra_flags=()) -> str:
@@ -47,7 +50,22 @@ def build(force: bool = True, extra_flags=()) -> str:
     if err.strip():
         print(err, file=sys.stderr)
     os.replace(tmp, LIB)
+    build_example()
     return LIB
+
+
+def build_example() -> str:
+    """The plain-C example program: gcc, linked against the library and the HIP runtime."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    tmp = EXAMPLE + f".tmp{os.getpid()}"
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), EXAMPLE_SRC, "-L", PKG, "-lswift_undo", "-L", os.path.join(rocm, "lib"),
+           "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", tmp]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + " ".join(cmd) + "\n" + res.stderr)
+    os.replace(tmp, EXAMPLE)
+    return EXAMPLE
 
 
 if __name__ == "__main__":

@@ -465,11 +465,37 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
 
 // ------------------------------------------------------------------------------------------
 // LAMB: step = moments + partial sums, norms, apply; undo = one launch.
-constexpr int kLambU = 4, kLambBlock = 64;     // pass 1 tile: 1,024 elements, one partial sum each
+// Launch shapes (one wavefront per tile): U 16-byte vectors per lane in pass 1 (one partial sum per
+// tile) and in pass 3.  The environment variables exist for sweeps.
+typedef void (*LambMomentsKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts, double2 *);
+typedef void (*LambApplyKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts, const double *);
+
+LambMomentsKernel pick_lamb_moments(int u, bool bf16) {
+  switch (u) {
+    case 1: return bf16 ? lamb_moments_kernel<true, 1, 64> : lamb_moments_kernel<false, 1, 64>;
+    case 2: return bf16 ? lamb_moments_kernel<true, 2, 64> : lamb_moments_kernel<false, 2, 64>;
+    default: return bf16 ? lamb_moments_kernel<true, 4, 64> : lamb_moments_kernel<false, 4, 64>;
+  }
+}
+
+LambApplyKernel pick_lamb_apply(int u) {
+  switch (u) {
+    case 1: return lamb_apply_kernel<1, 64>;
+    case 2: return lamb_apply_kernel<2, 64>;
+    default: return lamb_apply_kernel<4, 64>;
+  }
+}
+
+int clamp_u(long u) { return u <= 1 ? 1 : (u == 2 ? 2 : 4); }
 
 int lamb_prepare(Plan &plan, uint32_t tile_elems) {
   std::lock_guard<std::mutex> lock(plan.lamb_mu);
-  if (plan.lamb_spans) return SWIFT_OK;
+  if (plan.lamb_spans && plan.lamb_tile_elems == tile_elems) return SWIFT_OK;
+  if (plan.lamb_spans) {               // the pass-1 tile was changed (a sweep): rebuild the scratch
+    (void)hipFree(plan.lamb_spans);    // (hipFree waits for kernels that may still read it)
+    (void)hipFree(plan.lamb_partial);
+    plan.lamb_spans = plan.lamb_partial = nullptr;
+  }
   const uint64_t tpc = plan.chunk_elems / tile_elems;
   std::vector<TensorSpan> spans(plan.t_numel.size());
   for (size_t i = 0; i < spans.size(); ++i) {
@@ -517,25 +543,27 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
   std::shared_ptr<Plan> plan;
   if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const uint32_t tile1 = kLambU * kLambBlock * 4u, tile3 = 1u * 64u * 4u;
+  const int u1 = clamp_u(env_long("SWIFT_LAMB_U1", SWIFT_LAMB_U1)), u3 = clamp_u(env_long("SWIFT_LAMB_U3", SWIFT_LAMB_U3));
+  const uint32_t tile1 = (uint32_t)u1 * 256u, tile3 = (uint32_t)u3 * 256u, tileu = 256u;
   const uint32_t s1 = shift_for(tile1, plan->chunk_elems), s3 = shift_for(tile3, plan->chunk_elems);
+  const uint32_t su = shift_for(tileu, plan->chunk_elems);
   const uint64_t slots1 = (uint64_t)plan->n_chunks << s1, slots3 = (uint64_t)plan->n_chunks << s3;
-  const Tuning t1{kLambU, kLambBlock, (int)env_long("SWIFT_LAMB_WAVES_P1", SWIFT_LAMB_WAVES_P1)};
-  const Tuning t3{1, 64, (int)env_long("SWIFT_LAMB_WAVES_P3", SWIFT_LAMB_WAVES_P3)};
+  const uint64_t slotsu = (uint64_t)plan->n_chunks << su;
+  const Tuning t1{u1, 64, (int)env_long("SWIFT_LAMB_WAVES_P1", SWIFT_LAMB_WAVES_P1)};
+  const Tuning t3{u3, 64, (int)env_long("SWIFT_LAMB_WAVES_P3", SWIFT_LAMB_WAVES_P3)};
   const Tuning tu = opt_tuning(SWIFT_ADAMW, bf16);
   const ChunkDesc *chunks = static_cast<const ChunkDesc *>(plan->chunks());
   if (undo) {
     if (plan->n_chunks == 0) return SWIFT_OK;
     const auto k = bf16 ? lamb_undo_kernel<true, 1, 64> : lamb_undo_kernel<false, 1, 64>;
-    hipLaunchKernelGGL(k, dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64), lds_cap_bytes(info, tu),
-                       stream, chunks, slots3, s3, c, static_cast<const double *>(norms));
+    hipLaunchKernelGGL(k, dim3((uint32_t)std::min<uint64_t>(slotsu, 0x7fffffffull)), dim3(64), lds_cap_bytes(info, tu),
+                       stream, chunks, slotsu, su, c, static_cast<const double *>(norms));
     SWIFT_HIP(hipGetLastError());
     return SWIFT_OK;
   }
   if ((rc = lamb_prepare(*plan, tile1))) return rc;
   if (plan->n_chunks) {
-    const auto k1 = bf16 ? lamb_moments_kernel<true, kLambU, kLambBlock> : lamb_moments_kernel<false, kLambU, kLambBlock>;
-    hipLaunchKernelGGL(k1, dim3((uint32_t)std::min<uint64_t>(slots1, 0x7fffffffull)), dim3(kLambBlock),
+    hipLaunchKernelGGL(pick_lamb_moments(u1, bf16), dim3((uint32_t)std::min<uint64_t>(slots1, 0x7fffffffull)), dim3(64),
                        lds_cap_bytes(info, t1), stream, chunks, slots1, s1, c, static_cast<double2 *>(plan->lamb_partial));
     SWIFT_HIP(hipGetLastError());
   }
@@ -543,7 +571,7 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
                      static_cast<const TensorSpan *>(plan->lamb_spans), static_cast<const double2 *>(plan->lamb_partial), norms);
   SWIFT_HIP(hipGetLastError());
   if (plan->n_chunks) {
-    hipLaunchKernelGGL((lamb_apply_kernel<1, 64>), dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64),
+    hipLaunchKernelGGL(pick_lamb_apply(u3), dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64),
                        lds_cap_bytes(info, t3), stream, chunks, slots3, s3, c, static_cast<const double *>(norms));
     SWIFT_HIP(hipGetLastError());
   }

@@ -28,6 +28,8 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #define SWIFT_DEFAULT_WAVES_PER_CU 11
 #define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
 #define SWIFT_FUSED_WAVES_PER_CU 24     // step/undo fused with the digest
+#define SWIFT_LAMB_U1 4                 // LAMB pass 1: vectors per lane (tile = U * 256 elements)
+#define SWIFT_LAMB_U3 1                 // LAMB pass 3
 #define SWIFT_LAMB_WAVES_P1 6           // LAMB pass 1 (U = 4): wavefronts per CU
 #define SWIFT_LAMB_WAVES_P3 24          // LAMB pass 3 (3 streams in, 1 out)
 #define SWIFT_DEFAULT_DMASK_WGS_PER_CU 16384

@@ -470,3 +470,16 @@ def test_concurrent_callers_on_their_own_streams(B, synth):
             if x is not None:
                 assert all(np.array_equal(p.view(np.uint32), q.view(np.uint32)) for p, q in zip(x, y))
         check_against_oracle(k, HP[k], before_last, snapshot(s2), None, False, f"thread {j} final step")
+
+
+def test_plain_c_program_uses_the_library_without_python(B):
+    # the boundary is a C ABI: a C99 program (gcc) allocates with the HIP runtime, steps, digests, derives
+    # the mask and undoes, and checks the result itself
+    import os
+    import subprocess
+    from paper_2302_06173_amd import build
+    exe = build.EXAMPLE
+    assert os.path.exists(exe), "build the package first"
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stderr + out.stdout
+    assert out.stdout.startswith("ok:")
