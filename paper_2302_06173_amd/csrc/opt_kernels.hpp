@@ -1,11 +1,12 @@
 // Optimizer step / update-undo kernels for gfx950 (one multi-tensor launch per call).
 //
 // What is computed: Alg. 1 and Alg. 2 of the paper (SGD with momentum and its undo) and the
-// Adam / AdamW pairs of App. A.  How: every workgroup walks a flat chunk table with a grid
-// stride; a chunk is a run of up to `chunk_elems` elements of one tensor.  Each lane moves 16
-// bytes per stream per access (theta, g, m, v in; theta, m, v out), widens to binary64, applies
-// the update lines with explicit FMAs and rounds once on the way out.  The path is HBM-bound
-// (28 bytes per element for Adam with fp32 gradients), so there is no LDS staging and no MFMA.
+// Adam / AdamW pairs of App. A.  How: the tensor list is cut into a flat table of chunks (runs of
+// one tensor's elements); one 64-lane workgroup handles one tile of a chunk.  Each lane moves 16
+// bytes per stream (theta, g, m, v in; theta, m, v out), widens to binary64, applies the update
+// lines with explicit FMAs and rounds once on the way out.  The path is HBM-bound (28 bytes per
+// element for Adam with fp32 gradients, 0.7 flop per byte), so there is no LDS staging and no MFMA;
+// what matters is the order and the number of memory requests in flight (see opt_kernel below).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,15 +15,16 @@ namespace swift {
 
 constexpr int kSGDM = 0, kADAM = 1, kADAMW = 2;
 constexpr int kThreads = 256;           // 4 wavefronts of 64
-#ifndef SWIFT_DIGEST_U
-#define SWIFT_DIGEST_U 1                // digest kernel: 16-byte loads in flight per lane
-#define SWIFT_DIGEST_CHUNK 65536        // digest kernel: words per workgroup (large inputs)
-#endif
-// Launch shapes of the optimizer kernels that get compiled: X(U, BLOCK).
+// Launch shapes of the optimizer kernels that get compiled: X(U, BLOCK) = 16-byte vectors per lane,
+// lanes per workgroup.  The default is the measured best; the others serve sweeps.
 #ifndef SWIFT_SHAPES
 #define SWIFT_SHAPES(X) X(1, 64) X(2, 64) X(4, 64) X(1, 256)
 #endif
+// Tuning defaults, all measured on MI355X with the 7 B-parameter list (wavefronts per compute unit
+// are enforced through unused dynamic LDS).
 #ifndef SWIFT_DEFAULT_U
+#define SWIFT_DIGEST_U 1                // digest kernel: 16-byte loads in flight per lane
+#define SWIFT_DIGEST_CHUNK 65536        // digest kernel: words per workgroup (large inputs)
 #define SWIFT_DEFAULT_U 1
 #define SWIFT_DEFAULT_BLOCK 64
 #define SWIFT_DEFAULT_WAVES_PER_CU 11
