@@ -260,6 +260,25 @@ def main() -> int:
                         "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
         log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
 
+    # the same step and undo with a bfloat16 copy of theta written alongside (2 more bytes per parameter)
+    xb = [torch.empty(t.numel(), dtype=torch.bfloat16, device="cuda") for t in state.theta]
+    tl_xb = B.TensorList(state.theta, state.grad, state.m, state.v, param_bf16=xb)
+    for name, fn, bpe in (("adamw_step_bf16_copy", lambda: B.swift_opt_step(tl_xb, hp_w), 26 + g_bytes),
+                          ("adamw_undo_bf16_copy", lambda: B.swift_opt_undo(tl_xb, hp_w), 26 + g_bytes)):
+        reps = max(3, min(args.steps, 10))
+        fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for k in range(reps):
+            fn()
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[reps]) / reps
+        extras[name] = {"ms": round(ms, 4), "gparams_per_s": round(N / ms / 1e6, 2),
+                        "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
+        log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
+    del xb, tl_xb
+
     seg_ms = {s: 0.0 for s in segs}
     for ev in all_events:
         for k, s in enumerate(segs):

@@ -70,13 +70,19 @@ typedef struct {
   double eps;           /* >= 0           (Adam, AdamW) */
 } swift_hparams;
 
-/* A list of n tensors.  All five arrays are HOST arrays of length n; the pointers they hold are
+/* A list of n tensors.  All arrays are HOST arrays of length n; the pointers they hold are
  * DEVICE pointers to contiguous 1-D storage of numel[i] elements.  param, m, v: binary32,
  * 4-byte aligned, updated in place.  grad: binary32 (4-byte aligned) or bfloat16 (2-byte
  * aligned), NEVER written -- the undo needs it intact (paper, "Update-undo": only the latest
  * gradient is cached, no extra memory).  16-byte alignment of all of a tensor's pointers
- * (8-byte for bf16 gradients) selects the 128-bit access path; results are bit-identical either way.
- * v may be NULL for SWIFT_SGDM.  Tensors with numel 0 are allowed and skipped. */
+ * (8-byte for bfloat16 buffers) selects the 128-bit access path; results are bit-identical either way.
+ * v may be NULL for SWIFT_SGDM.  Tensors with numel 0 are allowed and skipped.
+ * param_bf16 (nullable array; not from the paper): mixed-precision training keeps a bfloat16 copy of
+ * the parameters next to the binary32 master weights.  If the array is given, swift_opt_step and
+ * swift_opt_undo (host- and device-mask forms) also write, for every tensor they touch, the bfloat16
+ * nearest to each new binary32 parameter (ties to even, NaN -> 0x7FC0) into param_bf16[i] (2-byte
+ * aligned, numel[i] elements, write only): 2 more bytes of traffic per parameter instead of a cast pass.
+ * The LAMB and fused-digest entry points do not take it (SWIFT_EINVAL). */
 typedef struct {
   int64_t n;
   void *const *param;
@@ -84,6 +90,7 @@ typedef struct {
   void *const *m;
   void *const *v;
   const int64_t *numel;
+  void *const *param_bf16;
 } swift_tensor_list;
 
 /* Optimizer step t: (x_t, g_t, m_{t-1}, v_{t-1}) -> (x_{t+1}, m_t, v_t) in place, for every

@@ -63,6 +63,8 @@ def _load():
         lib.oracle_lamb_step.argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p, p]
         lib.oracle_lamb_undo.argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p, p]
         lib.oracle_lamb_step.restype = lib.oracle_lamb_undo.restype = None
+        lib.oracle_bf16_round.argtypes = [i64, p, p]
+        lib.oracle_bf16_round.restype = None
         lib.oracle_digest.argtypes = [p, i64]
         lib.oracle_digest.restype = ctypes.c_uint64
         _lib = lib
@@ -193,6 +195,16 @@ def undo_list(hp: Hyper, xs: Sequence, gs: Sequence, ms: Sequence, vs: Optional[
               mask: Optional[Sequence] = None):
     """Undo every tensor marked as updated (the paper's per-parameter flag); the rest pass through."""
     return _walk(opt_undo, hp, xs, gs, ms, vs, mask)
+
+
+def bf16_round(x32) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) of a float32 array: nearest, ties to even, NaN -> 0x7FC0."""
+    x = np.ascontiguousarray(np.asarray(x32).reshape(-1))
+    if x.dtype != np.float32:
+        raise TypeError("oracle.bf16_round: need float32")
+    out = np.empty(x.size, dtype=np.uint16)
+    _load().oracle_bf16_round(x.size, _ptr(x), _ptr(out))
+    return out
 
 
 def words(a) -> np.ndarray:

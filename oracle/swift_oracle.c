@@ -27,6 +27,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <string.h>
 
 /* ------------------------------------------------------------------------- */
 /* Alg. 1 (SGD with Momentum): m_t = mu m_{t-1} + (1-tau)(g_t + lambda x_t);    */
@@ -194,6 +195,29 @@ void oracle_lamb_undo(int64_t n, const double *x_new, const double *g, const dou
         x_old[i] = (x_new[i] + eta * q * r) / (1.0 - eta * q * lambda);
         m_old[i] = (m_new[i] - (1.0 - beta1) * g[i]) / beta1;
         v_old[i] = (v_new[i] - (1.0 - beta2) * (g[i] * g[i])) / beta2;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* bfloat16 copy of binary32 parameters (mixed-precision training keeps one next to   */
+/* the fp32 master weights; not in the paper).  bfloat16 is the upper half of binary32 */
+/* (8 exponent bits, 7 fraction bits); the copy is the nearest bfloat16, ties to the   */
+/* value whose last fraction bit is 0; overflow rounds to infinity; every NaN becomes   */
+/* the quiet NaN 0x7FC0.                                                                */
+void oracle_bf16_round(int64_t n, const float *x, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t u;
+        memcpy(&u, &x[i], 4);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) {          /* NaN */
+            out[i] = 0x7FC0u;
+            continue;
+        }
+        uint32_t kept = u >> 16;                        /* truncated candidate */
+        uint32_t dropped = u & 0xFFFFu;                 /* the 16 bits that do not fit */
+        if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))
+            kept += 1u;                                 /* nearer neighbour is above, or tie and odd */
+        out[i] = (uint16_t)kept;                        /* a carry into the exponent is the right value */
     }
 }
 

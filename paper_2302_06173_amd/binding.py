@@ -37,7 +37,8 @@ class SwiftHparams(ctypes.Structure):
 class SwiftTensorList(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int64), ("param", ctypes.POINTER(ctypes.c_void_p)),
                 ("grad", ctypes.POINTER(ctypes.c_void_p)), ("m", ctypes.POINTER(ctypes.c_void_p)),
-                ("v", ctypes.POINTER(ctypes.c_void_p)), ("numel", ctypes.POINTER(ctypes.c_int64))]
+                ("v", ctypes.POINTER(ctypes.c_void_p)), ("numel", ctypes.POINTER(ctypes.c_int64)),
+                ("param_bf16", ctypes.POINTER(ctypes.c_void_p))]
 
 
 _P = ctypes.c_void_p
@@ -121,10 +122,15 @@ class TensorList:
     """Marshalled swift_tensor_list; keeps the tensors and the host arrays alive."""
 
     def __init__(self, param: Sequence[torch.Tensor], grad: Sequence[torch.Tensor], m: Sequence[torch.Tensor],
-                 v: Optional[Sequence[torch.Tensor]] = None):
+                 v: Optional[Sequence[torch.Tensor]] = None, param_bf16: Optional[Sequence[torch.Tensor]] = None):
         n = len(param)
-        if len(grad) != n or len(m) != n or (v is not None and len(v) != n):
+        if len(grad) != n or len(m) != n or (v is not None and len(v) != n) or \
+                (param_bf16 is not None and len(param_bf16) != n):
             raise ValueError("tensor lists differ in length")
+        if param_bf16 is not None:
+            for i, t in enumerate(param_bf16):
+                if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.numel() != param[i].numel():
+                    raise ValueError(f"tensor {i}: param_bf16 must be a contiguous CUDA bfloat16 tensor of the same size")
         self.grad_bf16 = n > 0 and grad[0].dtype == torch.bfloat16
         for i in range(n):
             group = [param[i], grad[i], m[i]] + ([v[i]] if v is not None else [])
@@ -138,7 +144,9 @@ class TensorList:
                 raise ValueError(f"tensor {i}: param, m and v must be float32")
             if grad[i].dtype != (torch.bfloat16 if self.grad_bf16 else torch.float32):
                 raise ValueError(f"tensor {i}: gradients must all be float32 or all bfloat16")
-        self._keep = (list(param), list(grad), list(m), None if v is None else list(v))
+        self._keep = (list(param), list(grad), list(m), None if v is None else list(v),
+                      None if param_bf16 is None else list(param_bf16))
+        self._xb = None if param_bf16 is None else _ptr_array(param_bf16)
         self._param, self._grad, self._m = _ptr_array(param), _ptr_array(grad), _ptr_array(m)
         self._v = None if v is None else _ptr_array(v)
         self._numel = (ctypes.c_int64 * n)(*[t.numel() for t in param])
@@ -147,7 +155,8 @@ class TensorList:
             n, ctypes.cast(self._param, ctypes.POINTER(_P)), ctypes.cast(self._grad, ctypes.POINTER(_P)),
             ctypes.cast(self._m, ctypes.POINTER(_P)),
             ctypes.cast(self._v, ctypes.POINTER(_P)) if self._v is not None else None,
-            ctypes.cast(self._numel, ctypes.POINTER(ctypes.c_int64)))
+            ctypes.cast(self._numel, ctypes.POINTER(ctypes.c_int64)),
+            ctypes.cast(self._xb, ctypes.POINTER(_P)) if self._xb is not None else None)
 
 
 def _host_mask(mask, n: int):

@@ -292,6 +292,8 @@ int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
     if (l->numel[i] == 0) continue;
     if (!l->param[i] || !l->grad[i] || !l->m[i] || (hasv && !l->v[i]))
       return fail(SWIFT_EINVAL, "tensor %lld has a NULL pointer", (long long)i);
+    if (l->param_bf16 && (!l->param_bf16[i] || ((uintptr_t)l->param_bf16[i] & 1)))
+      return fail(SWIFT_EINVAL, "tensor %lld: param_bf16 is NULL or not 2-byte aligned", (long long)i);
     if (((uintptr_t)l->param[i] & 3) || ((uintptr_t)l->m[i] & 3) || (hasv && ((uintptr_t)l->v[i] & 3)) ||
         ((uintptr_t)l->grad[i] & galign))
       return fail(SWIFT_EINVAL, "tensor %lld has a pointer that is not aligned to its element size", (long long)i);
@@ -307,8 +309,10 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   key.reserve(64 + (size_t)l->n * 41);
   key_add(key, (uint8_t)'O');
   key_add(key, dev);
+  const bool hasxb = l->param_bf16 != nullptr;
   key_add(key, (uint8_t)hasv);
   key_add(key, (uint8_t)bf16);
+  key_add(key, (uint8_t)hasxb);
   key_add(key, l->n);
   key_add(key, env_long("SWIFT_CHUNK_ELEMS", 0));
   for (int64_t i = 0; i < l->n; ++i) {
@@ -320,6 +324,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     key_add(key, l->grad[i]);
     key_add(key, l->m[i]);
     if (hasv) key_add(key, l->v[i]);
+    if (hasxb) key_add(key, l->param_bf16[i]);
   }
   if (auto hit = find_plan(key)) {
     *out = hit;
@@ -340,6 +345,8 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     if ((rc = check_device_range(l->grad[i], n * gsz, dev, "grad", i))) return rc;
     if ((rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
     if (hasv && (rc = check_device_range(l->v[i], n * 4, dev, "v", i))) return rc;
+    if (hasxb && (rc = check_device_range(l->param_bf16[i], n * 2, dev, "param_bf16", i))) return rc;
+    if (hasxb) iv.push_back({(uintptr_t)l->param_bf16[i], (uintptr_t)l->param_bf16[i] + n * 2, true});
     const uintptr_t x = (uintptr_t)l->param[i], g = (uintptr_t)l->grad[i], m = (uintptr_t)l->m[i];
     iv.push_back({x, x + n * 4, true});
     iv.push_back({g, g + n * gsz, false});
@@ -373,14 +380,17 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     char *x = static_cast<char *>(l->param[i]), *m = static_cast<char *>(l->m[i]);
     char *v = hasv ? static_cast<char *>(l->v[i]) : nullptr;
     const char *g = static_cast<const char *>(l->grad[i]);
+    char *xb = hasxb ? static_cast<char *>(l->param_bf16[i]) : nullptr;
     const uintptr_t bits = (uintptr_t)x | (uintptr_t)m | (uintptr_t)v;
-    const uint32_t vec_ok = ((bits & 15) == 0) && (((uintptr_t)g & (bf16 ? 7 : 15)) == 0);
+    const uint32_t vec_ok = ((bits & 15) == 0) && (((uintptr_t)g & (bf16 ? 7 : 15)) == 0) && (((uintptr_t)xb & 7) == 0);
     for (uint64_t off = 0; off < n; off += ce) {
       ChunkDesc d;
       d.x = reinterpret_cast<float *>(x + off * 4);
       d.g = g + off * gsz;
       d.m = reinterpret_cast<float *>(m + off * 4);
       d.v = hasv ? reinterpret_cast<float *>(v + off * 4) : nullptr;
+      d.xb = hasxb ? reinterpret_cast<uint16_t *>(xb + off * 2) : nullptr;
+      d.pad = 0;
       d.len = (uint32_t)std::min<uint64_t>(ce, n - off);
       d.tensor = (uint32_t)i;
       d.vec_ok = vec_ok;
@@ -399,21 +409,23 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
 typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const uint8_t *, const OptConsts);
 
 template <int U, int BLOCK>
-OptKernel pick_kernel_shape(int kind, bool undo, bool bf16) {
-#define SWIFT_PICK(K)                                                                                   \
-  (undo ? (bf16 ? opt_kernel<K, true, true, U, BLOCK> : opt_kernel<K, true, false, U, BLOCK>)           \
-        : (bf16 ? opt_kernel<K, false, true, U, BLOCK> : opt_kernel<K, false, false, U, BLOCK>))
+OptKernel pick_kernel_shape(int kind, bool undo, bool bf16, bool xb) {
+#define SWIFT_PICK3(K, UNDO_, BF_) (xb ? opt_kernel<K, UNDO_, BF_, true, U, BLOCK> : opt_kernel<K, UNDO_, BF_, false, U, BLOCK>)
+#define SWIFT_PICK(K)                                                             \
+  (undo ? (bf16 ? SWIFT_PICK3(K, true, true) : SWIFT_PICK3(K, true, false))       \
+        : (bf16 ? SWIFT_PICK3(K, false, true) : SWIFT_PICK3(K, false, false)))
   switch (kind) {
     case SWIFT_SGDM: return SWIFT_PICK(kSGDM);
     case SWIFT_ADAM: return SWIFT_PICK(kADAM);
     default: return SWIFT_PICK(kADAMW);
   }
 #undef SWIFT_PICK
+#undef SWIFT_PICK3
 }
 
 // The launch shapes that are compiled in.  Returns nullptr for any other (U, BLOCK).
-OptKernel pick_kernel(const Tuning &t, int kind, bool undo, bool bf16) {
-#define SWIFT_SHAPE(U_, B_) if (t.u == U_ && t.block == B_) return pick_kernel_shape<U_, B_>(kind, undo, bf16);
+OptKernel pick_kernel(const Tuning &t, int kind, bool undo, bool bf16, bool xb) {
+#define SWIFT_SHAPE(U_, B_) if (t.u == U_ && t.block == B_) return pick_kernel_shape<U_, B_>(kind, undo, bf16, xb);
   SWIFT_SHAPES(SWIFT_SHAPE)
 #undef SWIFT_SHAPE
   return nullptr;
@@ -434,7 +446,7 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   DeviceInfo info;
   if ((rc = device_info(dev, &info))) return rc;
   const Tuning tune = opt_tuning(hp->kind, hp->grad_dtype == SWIFT_BF16);
-  const OptKernel kernel = pick_kernel(tune, hp->kind, undo, hp->grad_dtype == SWIFT_BF16);
+  const OptKernel kernel = pick_kernel(tune, hp->kind, undo, hp->grad_dtype == SWIFT_BF16, l->param_bf16 != nullptr);
   if (!kernel) return fail(SWIFT_EINVAL, "launch shape U=%d BLOCK=%d is not compiled in", tune.u, tune.block);
   const uint32_t tile_elems = (uint32_t)tune.u * (uint32_t)tune.block * 4u;
   if (want_dmask && (rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
@@ -530,6 +542,7 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
   int rc = validate_hparams(hp, undo, &c);
   if (rc) return rc;
   if (hp->kind != SWIFT_LAMB) return fail(SWIFT_EINVAL, "swift_lamb_* needs kind = SWIFT_LAMB");
+  if (l && l->param_bf16) return fail(SWIFT_EINVAL, "swift_lamb_* does not write a bfloat16 parameter copy");
   if ((rc = validate_list(l, hp))) return rc;
   if (l->n == 0) return SWIFT_OK;
   if (!norms) return fail(SWIFT_EINVAL, "norms_device is NULL");
@@ -623,6 +636,7 @@ int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_
   int rc = validate_hparams(hp, undo, &c);
   if (rc) return rc;
   if (hp->kind == SWIFT_LAMB) return fail(SWIFT_EINVAL, "the fused digest entry points do not take LAMB");
+  if (l && l->param_bf16) return fail(SWIFT_EINVAL, "the fused digest entry points do not write a bfloat16 parameter copy");
   if ((rc = validate_list(l, hp))) return rc;
   if (l->n == 0) return SWIFT_OK;
   for (int64_t i = 0; i < l->n; ++i)

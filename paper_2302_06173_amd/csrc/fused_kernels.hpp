@@ -25,7 +25,7 @@ namespace swift {
 template <int KIND, bool UNDO>
 struct OptDigestOp {       // step or undo of one element + digest contributions of its new words
   static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
-  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV;
+  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = false;
   const OptConsts &c;
   uint32_t elem0;          // index of the chunk's first element inside its tensor
   uint64_t dx = 0, dm = 0, dv = 0;

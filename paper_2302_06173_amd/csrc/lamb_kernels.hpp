@@ -47,7 +47,7 @@ __device__ __forceinline__ double wave_sum_f64(double s) {
 
 // Pass 1 of the step: the moment recurrences (written back) and the running sums for the norms.
 struct LambMomentsOp {
-  static constexpr bool kLoadG = true, kHasV = true, kStoreX = false, kStoreM = true, kStoreV = true;
+  static constexpr bool kLoadG = true, kHasV = true, kStoreX = false, kStoreM = true, kStoreV = true, kStoreXB = false;
   const OptConsts &c;
   double sx = 0.0, su = 0.0;
   __device__ __forceinline__ void elem(uint32_t, float &xf, float gf, float &mf, float &vf) {
@@ -65,7 +65,7 @@ struct LambMomentsOp {
 
 // Pass 3 of the step: x <- x - (eta q)(r + lambda x), r from the stored new moments.
 struct LambApplyOp {
-  static constexpr bool kLoadG = false, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false;
+  static constexpr bool kLoadG = false, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false, kStoreXB = false;
   const OptConsts &c;
   double eta_q;
   __device__ __forceinline__ void elem(uint32_t, float &xf, float, float &mf, float &vf) {

@@ -44,15 +44,17 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-struct ChunkDesc {         // one per chunk of the optimizer kernels, 48 bytes, device resident
+struct ChunkDesc {         // one per chunk of the optimizer kernels, 64 bytes, device resident
   float *x;                // theta of the chunk's first element, in/out
   const void *g;           // gradient, fp32 or bf16, read only
   float *m;                // momentum buffer / first moment, in/out
   float *v;                // second moment, in/out (null for SGDM)
+  uint16_t *xb;            // bfloat16 copy of theta, out only (null if the caller keeps none)
   uint32_t len;            // elements in this chunk (the last chunk of a tensor is short)
   uint32_t tensor;         // index of the tensor in the caller's list (for the device mask)
-  uint32_t vec_ok;         // 1: all four pointers are aligned for the 128-bit path
+  uint32_t vec_ok;         // 1: every pointer is aligned for the 128-bit path
   uint32_t elem0;          // index of the chunk's first element inside its tensor (mod 2^32)
+  uint64_t pad;
 };
 
 struct ChunkRef {          // digest kernel: one per chunk, 8 bytes, device resident
@@ -111,6 +113,14 @@ __device__ __forceinline__ void buf_st4(__amdgpu_buffer_rsrc_t r, uint32_t byte_
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
 
+// Nearest bfloat16 (the upper half of binary32) of a binary32 value, ties to even, overflow to
+// infinity, every NaN to the quiet NaN 0x7FC0.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  const uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
 // One element.  The vector body and the scalar head/tail path both call this, so an element's
 // result bits do not depend on where it falls in a chunk or on pointer alignment.
 // u = m^ / (sqrt(v^) + eps) with m^ = m/(1-beta1^t), v^ = v/(1-beta2^t)   (App. A).
@@ -157,12 +167,13 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
 // An "op" tells process_tile which streams a kernel moves and what to do with one element:
 //   kLoadG, kHasV          gradient / second moment are read
 //   kStoreX, kStoreM, kStoreV   streams written back
+//   kStoreXB               the bfloat16 copy of the new theta is written too
 //   elem(i, x, g, m, v)    the arithmetic of element i of the chunk (may also accumulate into
 //                          members of the op)
-template <int KIND, bool UNDO>
+template <int KIND, bool UNDO, bool XB = false>
 struct OptOp {             // optimizer step or undo of one element
   static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
-  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV;
+  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = XB;
   const OptConsts &c;
   __device__ __forceinline__ void elem(uint32_t, float &x, float g, float &m, float &v) {
     update_elem<KIND, UNDO>(x, g, m, v, c);
@@ -179,6 +190,14 @@ __device__ __forceinline__ void update_vec4(Op &op, uint32_t j, f32x4 &x, const 
     m[k] = me;
     if constexpr (Op::kHasV) v[k] = ve;
   }
+}
+
+// The bfloat16 copy of vector j (4 consecutive elements): 8 bytes.
+__device__ __forceinline__ void buf_st_bf16x4(__amdgpu_buffer_rsrc_t r, uint32_t j, const f32x4 &val) {
+  u32x2 packed;
+  packed[0] = f32_to_bf16_bits(val[0]) | (f32_to_bf16_bits(val[1]) << 16);
+  packed[1] = f32_to_bf16_bits(val[2]) | (f32_to_bf16_bits(val[3]) << 16);
+  __builtin_amdgcn_raw_buffer_store_b64(packed, r, (int)(j * 8u), 0, SWIFT_STORE_AUX);
 }
 
 // Vector j (4 consecutive elements) of the chunk's gradient, widened to fp32.
@@ -211,6 +230,7 @@ __device__ __forceinline__ void process_scalar(Op &op, const ChunkDesc &d, uint3
   if constexpr (Op::kLoadG) ge = load_grad1<BF16G>(d.g, e);
   op.elem(e, xe, ge, me, ve);
   if constexpr (Op::kStoreX) st<false>(d.x + e, xe);
+  if constexpr (Op::kStoreXB) st<false>(d.xb + e, (uint16_t)f32_to_bf16_bits(xe));
   if constexpr (Op::kStoreM) st<false>(d.m + e, me);
   if constexpr (Op::kStoreV) st<false>(d.v + e, ve);
 }
@@ -228,6 +248,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(d.x, n4 * 16u), rm = make_rsrc(d.m, n4 * 16u);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(d.v, HASV ? n4 * 16u : 0u);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc(d.g, Op::kLoadG ? n4 * (BF16G ? 8u : 16u) : 0u);
+    const __amdgpu_buffer_rsrc_t rxb = make_rsrc(d.xb, Op::kStoreXB ? n4 * 8u : 0u);
     const uint32_t j0 = ti * TILE4;
     if (j0 + TILE4 <= n4) {                                      // full tile: no predicates
       f32x4 xr[U], gr[U], mr[U], vr[U];
@@ -244,6 +265,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
         const uint32_t j = j0 + u * BLOCK + tid;
         update_vec4(op, j, xr[u], gr[u], mr[u], vr[u]);
         if constexpr (Op::kStoreX) buf_st4(rx, j * 16u, xr[u]);
+        if constexpr (Op::kStoreXB) buf_st_bf16x4(rxb, j, xr[u]);
         if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr[u]);
         if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr[u]);
       }
@@ -254,6 +276,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
         f32x4 vr = HASV ? buf_ld4(rv, j * 16u) : f32x4{0.f, 0.f, 0.f, 0.f};
         update_vec4(op, j, xr, gr, mr, vr);
         if constexpr (Op::kStoreX) buf_st4(rx, j * 16u, xr);
+        if constexpr (Op::kStoreXB) buf_st_bf16x4(rxb, j, xr);
         if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr);
         if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr);
       }
@@ -290,12 +313,12 @@ __device__ __forceinline__ bool tensor_is_marked(const uint8_t *dmask, uint32_t 
 // achieved HBM bandwidth of the mixed read/write stream.
 // `dmask` (nullable) holds one byte per tensor in device memory: tiles of tensors whose byte is
 // zero are skipped; such launches use a capped grid and stride over the slots.
-template <int KIND, bool UNDO, bool BF16G, int U, int BLOCK>
+template <int KIND, bool UNDO, bool BF16G, bool XB, int U, int BLOCK>
 __global__ void __launch_bounds__(BLOCK)
 opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_shift,
            const uint8_t *__restrict__ dmask, const OptConsts c) {
   constexpr uint32_t TILE = U * BLOCK * 4u;                      // elements per tile
-  OptOp<KIND, UNDO> op{c};
+  OptOp<KIND, UNDO, XB> op{c};
   // The host launches at most n_slots workgroups, so the first pass needs no bounds test (and no
   // wait for n_slots before the chunk entry can be fetched).
   uint64_t w = blockIdx.x;
@@ -306,7 +329,7 @@ opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_
     //  whole entry with one round of scalar loads instead of the length first and the pointers later)
     if (ti * TILE >= d.len || d.x == nullptr) continue;          // slot past the end of a short chunk
     if (dmask != nullptr && !tensor_is_marked(dmask, d.tensor)) continue;
-    process_tile<OptOp<KIND, UNDO>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
+    process_tile<OptOp<KIND, UNDO, XB>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
   } while ((w += gridDim.x) < n_slots);
 }
 

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(B):
 def test_struct_layouts_match_the_header(B):
     # int32, int32, int64, 7 doubles / int64 + 5 pointers: no padding surprises
     assert ctypes.sizeof(B.SwiftHparams) == 4 + 4 + 8 + 7 * 8
-    assert ctypes.sizeof(B.SwiftTensorList) == 8 + 5 * 8
+    assert ctypes.sizeof(B.SwiftTensorList) == 8 + 6 * 8
     assert B.SwiftHparams.lr.offset == 16 and B.SwiftHparams.eps.offset == 64
 
 
@@ -51,7 +51,7 @@ def test_digest_count_is_host_arithmetic(B):
 
 
 def _call(B, fn, hp, n=0):
-    lst = B.SwiftTensorList(n, None, None, None, None, None)
+    lst = B.SwiftTensorList(n, None, None, None, None, None, None)
     return getattr(B._lib, fn)(ctypes.byref(lst), ctypes.byref(hp), None, None)
 
 
@@ -93,11 +93,11 @@ def test_not_invertible_is_an_undo_only_error(B):
 def test_null_and_negative_arguments(B):
     hp = B.hparams("adam", step=1, lr=0.1)
     assert B._lib.swift_opt_step(None, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
-    lst = B.SwiftTensorList(2, None, None, None, None, None)
+    lst = B.SwiftTensorList(2, None, None, None, None, None, None)
     assert B._lib.swift_opt_step(ctypes.byref(lst), None, None, None) == B.SWIFT_EINVAL
     assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert "NULL" in B.swift_last_error()
-    lst = B.SwiftTensorList(-1, None, None, None, None, None)
+    lst = B.SwiftTensorList(-1, None, None, None, None, None, None)
     assert B._lib.swift_opt_undo(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     # numel < 0, missing v for Adam, misaligned pointer: all caught on the host
     n = 1
@@ -108,17 +108,21 @@ def test_null_and_negative_arguments(B):
     four = (ctypes.c_int64 * 1)(4)
     c = lambda a: ctypes.cast(a, P)
     i64 = lambda a: ctypes.cast(a, ctypes.POINTER(ctypes.c_int64))
-    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), c(ptr), i64(neg))
+    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), c(ptr), i64(neg), None)
     assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
-    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), None, i64(four))
+    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), None, i64(four), None)
     assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert "v array" in B.swift_last_error()
-    lst = B.SwiftTensorList(n, c(odd), c(ptr), c(ptr), c(ptr), i64(four))
+    lst = B.SwiftTensorList(n, c(odd), c(ptr), c(ptr), c(ptr), i64(four), None)
     assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert "aligned" in B.swift_last_error()
     # bf16 gradients may sit on 2-byte boundaries, fp32 gradients may not
-    lst = B.SwiftTensorList(n, c(ptr), c(odd), c(ptr), c(ptr), i64(four))
+    lst = B.SwiftTensorList(n, c(ptr), c(odd), c(ptr), c(ptr), i64(four), None)
     assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    odd1 = (ctypes.c_void_p * 1)(0x1001)
+    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), c(ptr), i64(four), c(odd1))
+    assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "param_bf16" in B.swift_last_error()
     assert B._lib.swift_mask_from_digests(-1, 3, None, None, None, None) == B.SWIFT_EINVAL
     assert B._lib.swift_mask_from_digests(4, 0, None, None, None, None) == B.SWIFT_EINVAL
     assert B._lib.swift_mask_from_digests(4, 3, None, None, None, None) == B.SWIFT_EINVAL
@@ -157,7 +161,7 @@ def test_tracker_host_logic_without_a_gpu(B):
     assert B._lib.swift_tracker_create(3, None) == B.SWIFT_EINVAL
     assert B._lib.swift_tracker_create(3, ctypes.byref(h)) == B.SWIFT_OK and h.value
     hp = B.hparams("adamw", step=5, lr=1e-3)
-    lst = B.SwiftTensorList(0, None, None, None, None, None)
+    lst = B.SwiftTensorList(0, None, None, None, None, None, None)
     ids = (ctypes.c_int64 * 1)(0)
     # no iteration in progress yet
     assert B._lib.swift_tracker_step(h, ctypes.byref(lst), ids, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
@@ -168,7 +172,7 @@ def test_tracker_host_logic_without_a_gpu(B):
     assert B._lib.swift_tracker_step(h, ctypes.byref(lst), ids, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert B._lib.swift_tracker_step(h, None, ids, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert B._lib.swift_tracker_begin(h, 5) == B.SWIFT_OK
-    one = B.SwiftTensorList(1, None, None, None, None, None)
+    one = B.SwiftTensorList(1, None, None, None, None, None, None)
     bad = (ctypes.c_int64 * 1)(7)
     assert B._lib.swift_tracker_step(h, ctypes.byref(one), bad, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert "out of range" in B.swift_last_error()

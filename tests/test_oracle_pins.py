@@ -480,3 +480,32 @@ def test_digest_list_is_buffer_major_and_empty_cases():
     d0 = oracle.digest_list([a, e, b], 0)
     assert d0.size == 3 and d0[1] == 0
     assert oracle.digest_list([], 0).size == 0
+
+
+# --------------------------------------------------------------------------- bf16 copy
+def test_bf16_round_matches_torch_and_the_definition():
+    r = np.random.default_rng(31)
+    x = np.concatenate([
+        r.normal(0, 0.02, 5000).astype(np.float32),
+        (r.integers(0, 1 << 32, 20000, dtype=np.uint64).astype(np.uint32)).view(np.float32),   # any bit pattern
+        np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 3.4028235e38,
+                  1e-40, -1e-45, 65280.0, 65408.0], dtype=np.float32),
+    ])
+    got = oracle.bf16_round(x)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    nan = np.isnan(x)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert (got[nan] == 0x7FC0).all()
+    # the definition, value by value: the result is a nearest bfloat16, and on a tie the even one
+    fin = np.isfinite(x) & (np.abs(x) < 3e38)
+    xs = x[fin].astype(np.float64)
+    back = (got[fin].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    up = ((got[fin].astype(np.uint32) + 1) << 16).view(np.float32).astype(np.float64)
+    dn = ((got[fin].astype(np.uint32) - 1) << 16).view(np.float32).astype(np.float64)
+    with np.errstate(invalid="ignore"):
+        ok_near = (np.abs(back - xs) <= np.abs(up - xs)) | ~np.isfinite(up)
+        ok_near &= (np.abs(back - xs) <= np.abs(dn - xs)) | ~np.isfinite(dn) | (got[fin] == 0) | (got[fin] == 0x8000)
+    assert ok_near.all()
+    tie = np.array([1.00390625, 1.01171875], dtype=np.float32)    # halfway between neighbours: 0x3F80|0x3F81 and 0x3F81|0x3F82
+    assert oracle.bf16_round(tie).tolist() == [0x3F80, 0x3F82]
+    assert oracle.bf16_round(np.array([3.4028235e38], np.float32))[0] == 0x7F80   # rounds up to infinity
