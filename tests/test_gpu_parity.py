@@ -483,3 +483,24 @@ def test_plain_c_program_uses_the_library_without_python(B):
     out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert out.returncode == 0, out.stderr + out.stdout
     assert out.stdout.startswith("ok:")
+
+
+def test_stream_copy_is_exact_and_checks_its_arguments(B):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    for n in (16, 1024, 4096 * 3 + 16, (1 << 24) + 4096):
+        src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda", generator=gen)
+        dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+        B.swift_stream_copy(dst[:n], src)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and not dst[n:].any()
+    big = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_stream_copy(big[16:2064], big[0:2048])            # overlapping ranges
+    assert e.value.code == B.SWIFT_EINVAL and "overlap" in e.value.message
+    with pytest.raises(B.SwiftError):
+        B.swift_stream_copy(big[8:2056], big[2048:4096])           # destination not 16-byte aligned
+    with pytest.raises(B.SwiftError):
+        B.swift_stream_copy(big[0:24], big[2048:2072])             # not a multiple of 16 bytes
+    with pytest.raises(B.SwiftError):
+        B.swift_stream_copy(big[0:2048], torch.zeros(2048, dtype=torch.uint8))   # host source
