@@ -6,8 +6,9 @@ resident in HBM before the clock starts:
 
   1. digest of theta, m, v per tensor                       (state at iteration t)
   2. AdamW step on a seeded random half of the tensors      (an update interrupted by a failure)
-  3. digest again, 4. per-tensor "updated" mask from the two digest arrays (on the device)
-  5. AdamW undo of exactly the marked tensors               (selective undo)
+  3. digest again, 4. per-tensor "updated" mask from the two digest arrays (on the device), copied
+     to the host (one byte per tensor: the only synchronisation of the pass)
+  5. AdamW undo of exactly the marked tensors               (selective undo, grid sized to them)
   6. full AdamW step + full AdamW undo
   7. full Adam (coupled decay) step + undo
   8. full SGD-momentum step + undo (theta, g, m only)
@@ -115,7 +116,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_adamw")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=128 * 1024 * 1024)
+    ap.add_argument("--cpu-sample", type=int, default=256 * 1024 * 1024)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="only run swift_stream_copy on BYTES bytes five times (a copy of known size, to "
                          "scale a profiler's HBM byte counters) and exit")
@@ -198,8 +199,9 @@ def main() -> int:
         B.swift_state_digest(bufs, 0, out=d0); mark()
         B.swift_opt_step(tl_adam, hps["adamw"], host_mask=mask); mark()
         B.swift_state_digest(bufs, 0, out=d1); mark()
-        B.swift_mask_from_digests(d0, d1, n_t, out=dmask); mark()
-        B.swift_opt_undo_dmask(tl_adam, hps["adamw"], dmask); mark()
+        B.swift_mask_from_digests(d0, d1, n_t, out=dmask)
+        found = dmask.cpu().tolist(); mark()          # n_t bytes to the host: the only synchronisation of the pass
+        B.swift_opt_undo(tl_adam, hps["adamw"], host_mask=found); mark()
         B.swift_opt_step(tl_adam, hps["adamw"]); mark()
         B.swift_opt_undo(tl_adam, hps["adamw"]); mark()
         B.swift_opt_step(tl_adam, hps["adam"]); mark()
@@ -222,74 +224,55 @@ def main() -> int:
         log("[bench] ERROR: digest-derived mask differs from the step mask")
         return 1
 
-    # Outside the timed pass and outside `value`: LAMB step (three launches, 40 bytes per parameter)
-    # and its saved-norm undo (28 bytes per parameter), reported under "extras".
+    # Outside the timed pass and outside `value`, reported under "extras": LAMB step (three launches,
+    # 40 bytes per parameter) and its saved-norm undo; step / undo that also return the digests; step /
+    # undo that also write a bfloat16 copy of theta; the selective undo with the mask left on the device.
     extras = {}
+
+    def extra(name, fn, bytes_per_param, n_params=N):
+        reps = max(3, min(args.steps, 10))
+        fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for k in range(reps):
+            fn()
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[reps]) / reps
+        extras[name] = {"ms": round(ms, 4), "gparams_per_s": round(n_params / ms / 1e6, 2),
+                        "gb_per_s": round(bytes_per_param * n_params / ms / 1e6, 1), "bytes_per_param": bytes_per_param}
+        log(f"[bench] {name:26s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
+
+    hp_w = hps["adamw"]
     if not bf16:
         hp_lamb = B.hparams("lamb", step=t_step, lr=2e-3, weight_decay=0.01, beta1=0.9, beta2=0.999, eps=1e-6)
         norms = torch.zeros(2 * n_t, dtype=torch.float64, device="cuda")
-        for name, fn, bpe in (("lamb_step", lambda: B.swift_lamb_step(tl_adam, hp_lamb, norms), 40),
-                              ("lamb_undo", lambda: B.swift_lamb_undo(tl_adam, hp_lamb, norms), 28)):
-            reps = max(3, min(args.steps, 10))
-            fn()
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-            ev[0].record()
-            for k in range(reps):
-                fn()
-                ev[k + 1].record()
-            torch.cuda.synchronize()
-            ms = ev[0].elapsed_time(ev[reps]) / reps
-            extras[name] = {"ms": round(ms, 4), "gparams_per_s": round(N / ms / 1e6, 2),
-                            "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
-            log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
-
-    hp_w = hps["adamw"]
+        extra("lamb_step", lambda: B.swift_lamb_step(tl_adam, hp_lamb, norms), 40)
+        extra("lamb_undo", lambda: B.swift_lamb_undo(tl_adam, hp_lamb, norms), 28)
     dig = torch.zeros(3 * n_t, dtype=torch.int64, device="cuda")
-    for name, fn, bpe in (("adamw_step_with_digest", lambda: B.swift_opt_step_digest(tl_adam, hp_w, dig), 24 + g_bytes),
-                          ("adamw_undo_with_digest", lambda: B.swift_opt_undo_digest(tl_adam, hp_w, dig), 24 + g_bytes)):
-        reps = max(3, min(args.steps, 10))
-        fn()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-        ev[0].record()
-        for k in range(reps):
-            fn()
-            ev[k + 1].record()
-        torch.cuda.synchronize()
-        ms = ev[0].elapsed_time(ev[reps]) / reps
-        extras[name] = {"ms": round(ms, 4), "gparams_per_s": round(N / ms / 1e6, 2),
-                        "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
-        log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
-
-    # the same step and undo with a bfloat16 copy of theta written alongside (2 more bytes per parameter)
+    extra("adamw_step_with_digest", lambda: B.swift_opt_step_digest(tl_adam, hp_w, dig), 24 + g_bytes)
+    extra("adamw_undo_with_digest", lambda: B.swift_opt_undo_digest(tl_adam, hp_w, dig), 24 + g_bytes)
     xb = [torch.empty(t.numel(), dtype=torch.bfloat16, device="cuda") for t in state.theta]
     tl_xb = B.TensorList(state.theta, state.grad, state.m, state.v, param_bf16=xb)
-    for name, fn, bpe in (("adamw_step_bf16_copy", lambda: B.swift_opt_step(tl_xb, hp_w), 26 + g_bytes),
-                          ("adamw_undo_bf16_copy", lambda: B.swift_opt_undo(tl_xb, hp_w), 26 + g_bytes)):
-        reps = max(3, min(args.steps, 10))
-        fn()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-        ev[0].record()
-        for k in range(reps):
-            fn()
-            ev[k + 1].record()
-        torch.cuda.synchronize()
-        ms = ev[0].elapsed_time(ev[reps]) / reps
-        extras[name] = {"ms": round(ms, 4), "gparams_per_s": round(N / ms / 1e6, 2),
-                        "gb_per_s": round(bpe * N / ms / 1e6, 1), "bytes_per_param": bpe}
-        log(f"[bench] {name:22s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
+    extra("adamw_step_bf16_copy", lambda: B.swift_opt_step(tl_xb, hp_w), 26 + g_bytes)
+    extra("adamw_undo_bf16_copy", lambda: B.swift_opt_undo(tl_xb, hp_w), 26 + g_bytes)
     del xb, tl_xb
 
-    seg_ms = {s: 0.0 for s in segs}
-    for ev in all_events:
-        for k, s in enumerate(segs):
-            seg_ms[s] += ev[k].elapsed_time(ev[k + 1])
-    seg_ms = {s: v / max(args.steps, 1) for s, v in seg_ms.items()}
+    def masked_pair():
+        B.swift_opt_step_dmask(tl_adam, hp_w, dmask)
+        B.swift_opt_undo_dmask(tl_adam, hp_w, dmask)
+    extra("adamw_step_undo_device_mask", masked_pair, 24 + g_bytes, 2 * n_masked)
+
+    seg_all = {s: sorted(ev[k].elapsed_time(ev[k + 1]) for ev in all_events) for k, s in enumerate(segs)}
+    seg_ms = {s: sum(v) / max(len(v), 1) for s, v in seg_all.items()}
     params_per_pass = sum(seg_params.values())
     value = params_per_pass * args.steps / wall
     kernels = {}
     for s in segs:
         ms = seg_ms[s]
-        kernels[s] = {"ms": round(ms, 4), "gparams_per_s": round(seg_params[s] / ms / 1e6, 2) if ms > 0 else None,
+        kernels[s] = {"ms": round(ms, 4), "ms_median": round(seg_all[s][len(seg_all[s]) // 2], 4),
+                      "ms_best": round(seg_all[s][0], 4),
+                      "gparams_per_s": round(seg_params[s] / ms / 1e6, 2) if ms > 0 else None,
                       "gb_per_s": round(seg_bytes[s] / ms / 1e6, 1) if ms > 0 else None}
         log(f"[bench] {s:22s} {ms:9.3f} ms  {kernels[s]['gparams_per_s']} Gparam/s  {kernels[s]['gb_per_s']} GB/s")
     # The AdamW undo kernel is launched twice per pass (selective undo of the marked half, then the

@@ -119,9 +119,13 @@ int swift_opt_step(const swift_tensor_list *list, const swift_hparams *hp,
 int swift_opt_undo(const swift_tensor_list *list, const swift_hparams *hp,
                    const uint8_t *host_mask, void *hip_stream);
 
-/* The same two operations with the "updated" marks in DEVICE memory (n bytes, not nullable), read
- * by the kernel when it runs: the mask can be produced by swift_mask_from_digests on the same
- * stream with no host round trip. */
+/* The same two operations with the "updated" marks in DEVICE memory (n bytes, not nullable, left
+ * unchanged), read on the device when the call's kernels run: the mask can be produced by
+ * swift_mask_from_digests on the same stream with no host round trip.  A small kernel packs the
+ * work list by the mask into scratch memory the library keeps for this tensor list (allocated on
+ * the first such call); calls on the same list must not overlap, as for any call that writes the
+ * same tensors.  Since the host cannot size the launch to the marked tensors, these calls reach
+ * somewhat lower bandwidth than the host-mask ones; prefer those when the host knows the marks. */
 int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
                          const uint8_t *device_mask, void *hip_stream);
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp,

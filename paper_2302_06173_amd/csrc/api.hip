@@ -14,6 +14,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "swift_undo.h"
@@ -99,6 +100,9 @@ struct Plan {
   // fused step/undo + digest only, created on first use (guarded by lamb_mu): chunk spans and slots
   void *fused_spans = nullptr;
   void *fused_slots = nullptr;
+  // device-mask calls only, created on first use (guarded by lamb_mu): [tensor spans | packed chunk table | slot count]
+  void *packed_mem = nullptr;
+  size_t packed_table_off = 0, packed_count_off = 0;
   const void *descs() const { return dev_mem; }
   const void *chunks() const { return static_cast<const char *>(dev_mem) + desc_bytes; }
   ~Plan() {
@@ -110,6 +114,7 @@ struct Plan {
       if (lamb_partial) (void)hipFree(lamb_partial);
       if (fused_spans) (void)hipFree(fused_spans);
       if (fused_slots) (void)hipFree(fused_slots);
+      if (packed_mem) (void)hipFree(packed_mem);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     }
   }
@@ -117,30 +122,37 @@ struct Plan {
 
 constexpr size_t kMaxPlans = 256;   // a layer-wise training loop keeps one plan per layer
 std::mutex g_plan_mu;
-std::list<std::shared_ptr<Plan>> *g_plans = nullptr;   // most recently used first; leaked at exit on purpose
+struct PlanCache {
+  std::list<std::shared_ptr<Plan>> lru;                                               // most recently used first
+  std::unordered_map<std::string, std::list<std::shared_ptr<Plan>>::iterator> index;  // key -> position in lru
+};
+PlanCache *g_plans = nullptr;   // leaked at exit on purpose: the HIP runtime may already be gone by then
 
 std::shared_ptr<Plan> find_plan(const std::string &key) {
   std::lock_guard<std::mutex> lock(g_plan_mu);
-  if (!g_plans) g_plans = new std::list<std::shared_ptr<Plan>>();
-  for (auto it = g_plans->begin(); it != g_plans->end(); ++it) {
-    if ((*it)->key == key) {
-      auto p = *it;
-      g_plans->erase(it);
-      g_plans->push_front(p);
-      return p;
-    }
-  }
-  return nullptr;
+  if (!g_plans) g_plans = new PlanCache();
+  auto hit = g_plans->index.find(key);
+  if (hit == g_plans->index.end()) return nullptr;
+  g_plans->lru.splice(g_plans->lru.begin(), g_plans->lru, hit->second);   // iterators stay valid
+  return *hit->second;
 }
 
 void keep_plan(const std::shared_ptr<Plan> &p) {
   std::shared_ptr<Plan> dropped;   // destroyed (hipFree) outside the lock
   std::lock_guard<std::mutex> lock(g_plan_mu);
-  if (!g_plans) g_plans = new std::list<std::shared_ptr<Plan>>();
-  g_plans->push_front(p);
-  if (g_plans->size() > kMaxPlans) {
-    dropped = g_plans->back();
-    g_plans->pop_back();
+  if (!g_plans) g_plans = new PlanCache();
+  auto hit = g_plans->index.find(p->key);
+  if (hit != g_plans->index.end()) {            // another thread built the same plan meanwhile: replace it
+    dropped = *hit->second;
+    g_plans->lru.erase(hit->second);
+    g_plans->index.erase(hit);
+  }
+  g_plans->lru.push_front(p);
+  g_plans->index[p->key] = g_plans->lru.begin();
+  if (g_plans->lru.size() > kMaxPlans) {        // cannot coincide with the replacement above: that kept the size
+    dropped = g_plans->lru.back();
+    g_plans->index.erase(dropped->key);
+    g_plans->lru.pop_back();
   }
 }
 
@@ -406,7 +418,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   return SWIFT_OK;
 }
 
-typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const uint8_t *, const OptConsts);
+typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const uint64_t *, const OptConsts);
 
 template <int U, int BLOCK>
 OptKernel pick_kernel_shape(int kind, bool undo, bool bf16, bool xb) {
@@ -431,8 +443,33 @@ OptKernel pick_kernel(const Tuning &t, int kind, bool undo, bool bf16, bool xb) 
   return nullptr;
 }
 
+// Scratch of the device-mask calls: where each tensor's chunks sit, room for the packed table and
+// its slot count.  Calls that share a plan (the same tensors) share it, like the tensors themselves.
+int packed_prepare(Plan &plan) {
+  std::lock_guard<std::mutex> lock(plan.lamb_mu);
+  if (plan.packed_mem) return SWIFT_OK;
+  std::vector<TensorChunks> spans(plan.t_numel.size());
+  for (size_t i = 0; i < spans.size(); ++i) {
+    spans[i].first = (uint32_t)plan.t_first_chunk[i];
+    spans[i].count = (uint32_t)((plan.t_numel[i] + plan.chunk_elems - 1) / plan.chunk_elems);
+  }
+  const size_t table_off = (spans.size() * sizeof(TensorChunks) + 255) & ~size_t(255);
+  const size_t count_off = table_off + std::max<size_t>(plan.n_chunks, 1) * sizeof(ChunkDesc);
+  void *mem = nullptr;
+  SWIFT_HIP(hipMalloc(&mem, count_off + 256));
+  hipError_t e = hipMemcpy(mem, spans.data(), spans.size() * sizeof(TensorChunks), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(mem);
+    return fail(SWIFT_EHIP, "device-mask scratch upload failed: %s", hipGetErrorName(e));
+  }
+  plan.packed_table_off = table_off;
+  plan.packed_count_off = count_off;
+  plan.packed_mem = mem;
+  return SWIFT_OK;
+}
+
 int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask,
-             const uint8_t *device_mask, bool want_dmask, bool undo, void *stream) {
+             const uint8_t *device_mask, bool want_dmask, bool undo, void *stream_) {
   OptConsts c;
   int rc = validate_hparams(hp, undo, &c);
   if (rc) return rc;
@@ -456,21 +493,32 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   uint32_t tpc_shift = 0;
   while ((tile_elems << tpc_shift) < plan->chunk_elems) ++tpc_shift;
   const uint64_t n_slots = (uint64_t)plan->n_chunks << tpc_shift;
+  const hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const ChunkDesc *table = static_cast<const ChunkDesc *>(plan->chunks());
+  const uint64_t *n_slots_dev = nullptr;
   uint64_t grid_cap = 0x7fffffffull;
   if (want_dmask) {
-    // With a device mask the host cannot size the grid to the marked tensors, and every skipped
-    // tile still costs a dispatch (about 0.9 ns).  A grid capped at about two thirds of a large
-    // list, strided over, measured best for half-marked lists (6.1 against 5.7 TB/s on the 7B
-    // list) and nearly halves the cost of an almost empty mask.  Callers with a sparse mask and
-    // no reason to avoid a host round trip should prefer the host-mask entry points, whose grid
-    // covers the marked tensors only.
+    // The host cannot size the grid to the marked tensors, and a workgroup that finds nothing to do
+    // still costs a dispatch (about 0.9 ns) plus the latency of the table fetch it needed to find
+    // that out.  So a small kernel first packs the chunk table by the mask, entirely on the device,
+    // and leaves the slot count beside it; the update kernel then runs over the packed table with a
+    // capped grid, strides, and stops at that count: every pass of its loop has a tile to process,
+    // and an almost empty mask costs at most the capped grid's idle dispatches.
+    if ((rc = packed_prepare(*plan))) return rc;
+    char *pm = static_cast<char *>(plan->packed_mem);
+    ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(pm + plan->packed_table_off);
+    uint64_t *count = reinterpret_cast<uint64_t *>(pm + plan->packed_count_off);
     const long per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
     if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
+    hipLaunchKernelGGL(compact_chunks_kernel, dim3((uint32_t)l->n), dim3(kThreads), 0, stream, table,
+                       reinterpret_cast<const TensorChunks *>(pm), (uint32_t)l->n, device_mask, tpc_shift, packed, count);
+    SWIFT_HIP(hipGetLastError());
+    table = packed;
+    n_slots_dev = count;
   }
   const uint32_t grid = (uint32_t)std::min<uint64_t>(n_slots, grid_cap);
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3((uint32_t)tune.block), lds_cap_bytes(info, tune),
-                     static_cast<hipStream_t>(stream), static_cast<const ChunkDesc *>(plan->chunks()), n_slots,
-                     tpc_shift, device_mask, c);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3((uint32_t)tune.block), lds_cap_bytes(info, tune), stream, table, n_slots,
+                     tpc_shift, n_slots_dev, c);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }
@@ -1060,7 +1108,10 @@ int swift_shutdown(void) {
   std::list<std::shared_ptr<Plan>> drop;
   {
     std::lock_guard<std::mutex> lock(g_plan_mu);
-    if (g_plans) drop.swap(*g_plans);
+    if (g_plans) {
+      drop.swap(g_plans->lru);
+      g_plans->index.clear();
+    }
   }
   drop.clear();   // ~Plan frees (and thereby synchronises) on each plan's device
   return SWIFT_OK;

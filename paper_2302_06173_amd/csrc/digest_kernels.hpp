@@ -147,4 +147,54 @@ mask_from_digests_kernel(uint32_t n_tensors, uint32_t n_groups, const uint64_t *
   }
 }
 
+// Where a tensor's chunks sit in the optimizer chunk table.
+struct TensorChunks {
+  uint32_t first, count;
+};
+
+// Packs an optimizer chunk table by a device-resident mask (one byte per tensor, nonzero = marked),
+// so that a launch over the packed table touches marked tensors only without the host ever seeing
+// the mask.  One workgroup per tensor.  With A = chunks of marked tensors before this one, I =
+// chunks of unmarked tensors before it and T = chunks of all marked tensors, a marked tensor's
+// entries are copied to packed[A ...) (list order is kept) and an unmarked tensor writes empty
+// entries to packed[T + I ...): every entry of `packed` is written, so nothing of an earlier call
+// survives.  *n_slots_out = T << tpc_shift, the number of tile slots the packed table holds.
+__global__ void __launch_bounds__(kThreads)
+compact_chunks_kernel(const ChunkDesc *__restrict__ chunks, const TensorChunks *__restrict__ spans, uint32_t n_tensors,
+                      const uint8_t *__restrict__ mask, uint32_t tpc_shift, ChunkDesc *__restrict__ packed,
+                      uint64_t *__restrict__ n_slots_out) {
+  __shared__ uint64_t part[3][kThreads / 64];
+  const uint32_t t = blockIdx.x, tid = threadIdx.x;
+  uint64_t marked_before = 0, unmarked_before = 0, marked_total = 0;
+  for (uint32_t j = tid; j < n_tensors; j += kThreads) {
+    const uint64_t cnt = spans[j].count;
+    if (mask[j] != 0) {
+      marked_total += cnt;
+      if (j < t) marked_before += cnt;
+    } else if (j < t) {
+      unmarked_before += cnt;
+    }
+  }
+  const uint64_t s0 = wave_sum_u64(marked_before), s1 = wave_sum_u64(unmarked_before), s2 = wave_sum_u64(marked_total);
+  if ((tid & 63u) == 0) {
+    part[0][tid >> 6] = s0;
+    part[1][tid >> 6] = s1;
+    part[2][tid >> 6] = s2;
+  }
+  __syncthreads();
+  uint64_t sum[3] = {0, 0, 0};
+#pragma unroll
+  for (int k = 0; k < 3; ++k)
+#pragma unroll
+    for (int wv = 0; wv < kThreads / 64; ++wv) sum[k] += part[k][wv];
+  const bool marked = mask[t] != 0;
+  const TensorChunks sp = spans[t];
+  const uint64_t dst = marked ? sum[0] : sum[2] + sum[1];
+  ChunkDesc empty;
+  empty.x = nullptr; empty.g = nullptr; empty.m = nullptr; empty.v = nullptr; empty.xb = nullptr;
+  empty.len = 0; empty.tensor = t; empty.vec_ok = 0; empty.elem0 = 0; empty.pad = 0;
+  for (uint32_t k = tid; k < sp.count; k += kThreads) packed[dst + k] = marked ? chunks[sp.first + k] : empty;
+  if (t == 0 && tid == 0) *n_slots_out = sum[2] << tpc_shift;
+}
+
 }  // namespace swift

@@ -210,6 +210,40 @@ def test_host_mask_and_device_mask(B, synth, kind):
             assert all(np.array_equal(p.view(np.uint32), q.view(np.uint32)) for p, q in zip(x, y))
 
 
+def test_successive_device_masks_on_one_list(B, synth):
+    # The device-mask calls pack the chunk table by the mask on the device and keep that scratch with
+    # the list's plan: a later call with another mask (fewer, more, none or all tensors marked; any
+    # nonzero byte marks) must see nothing of the earlier one.  Reference: the host-mask call on a
+    # clone, itself checked against the oracle once.
+    kind = "adamw"
+    shapes = [(70001,), (3,), (0,), (16384,), (5000,), (33333,), (1,), (8192,), (20000,), (4099,)]
+    n = len(shapes)
+    masks = [[1, 0, 0, 1, 1, 0, 1, 0, 1, 1], [0] * n, [0, 0, 0, 0, 0, 0, 1, 0, 0, 0], [1] * n,
+             [0, 7, 255, 0, 0, 2, 0, 128, 0, 0], [1, 1, 0, 0, 0, 0, 0, 0, 0, 1]]
+    a = make(synth, kind, shapes, seed=31)
+    b = a.clone()
+    hp = binding_hparams(B, kind, HP[kind])
+    tla, tlb = tensor_list(B, a), tensor_list(B, b)
+    for k, mask in enumerate(masks):
+        dm = torch.tensor(mask, dtype=torch.uint8, device="cuda")
+        undo = k % 3 == 2
+        pre = snapshot(a)
+        if undo:
+            B.swift_opt_undo(tla, hp, host_mask=[1 if v else 0 for v in mask])
+            B.swift_opt_undo_dmask(tlb, hp, dm)
+        else:
+            B.swift_opt_step(tla, hp, host_mask=[1 if v else 0 for v in mask])
+            B.swift_opt_step_dmask(tlb, hp, dm)
+        torch.cuda.synchronize()
+        pa, pb = snapshot(a), snapshot(b)
+        if k == 0:
+            check_against_oracle(kind, HP[kind], pre, pa, mask, False, "adamw masked step")
+        for x, y in zip(pa, pb):
+            for p, q in zip(x, y):
+                assert np.array_equal(p.view(np.uint32), q.view(np.uint32)), f"call {k} mask {mask}"
+        assert np.array_equal(dm.cpu().numpy(), np.array(mask, np.uint8))      # the mask itself is read only
+
+
 def test_special_values_and_degenerate_hyper_parameters(B, synth):
     # NaN / Inf propagate as in IEEE arithmetic, denormals survive, -0.0 is kept, mu = 0 works
     n = 4096 + 64
