@@ -21,7 +21,7 @@ in; theta, m, v out) over the mean launch duration, measured with HIP events on 
 stream inside the timed region.
 `cpu_baseline` times the fp64 CPU oracle on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--no-extras]
 """
 from __future__ import annotations
 
@@ -116,6 +116,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_adamw")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the launches reported under 'extras' (a profile of such a run holds the timed pass only)")
     ap.add_argument("--cpu-sample", type=int, default=256 * 1024 * 1024)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="only run swift_stream_copy on BYTES bytes five times (a copy of known size, to "
@@ -244,7 +246,10 @@ def main() -> int:
         log(f"[bench] {name:26s} {ms:9.3f} ms  {extras[name]['gparams_per_s']} Gparam/s  {extras[name]['gb_per_s']} GB/s")
 
     hp_w = hps["adamw"]
-    if not bf16:
+    if args.no_extras:
+        def extra(*a, **k):
+            return None
+    if not bf16 and not args.no_extras:
         hp_lamb = B.hparams("lamb", step=t_step, lr=2e-3, weight_decay=0.01, beta1=0.9, beta2=0.999, eps=1e-6)
         norms = torch.zeros(2 * n_t, dtype=torch.float64, device="cuda")
         extra("lamb_step", lambda: B.swift_lamb_step(tl_adam, hp_lamb, norms), 40)
@@ -252,8 +257,8 @@ def main() -> int:
     dig = torch.zeros(3 * n_t, dtype=torch.int64, device="cuda")
     extra("adamw_step_with_digest", lambda: B.swift_opt_step_digest(tl_adam, hp_w, dig), 24 + g_bytes)
     extra("adamw_undo_with_digest", lambda: B.swift_opt_undo_digest(tl_adam, hp_w, dig), 24 + g_bytes)
-    xb = [torch.empty(t.numel(), dtype=torch.bfloat16, device="cuda") for t in state.theta]
-    tl_xb = B.TensorList(state.theta, state.grad, state.m, state.v, param_bf16=xb)
+    xb = [torch.empty(0 if args.no_extras else t.numel(), dtype=torch.bfloat16, device="cuda") for t in state.theta]
+    tl_xb = None if args.no_extras else B.TensorList(state.theta, state.grad, state.m, state.v, param_bf16=xb)
     extra("adamw_step_bf16_copy", lambda: B.swift_opt_step(tl_xb, hp_w), 26 + g_bytes)
     extra("adamw_undo_bf16_copy", lambda: B.swift_opt_undo(tl_xb, hp_w), 26 + g_bytes)
     del xb, tl_xb

@@ -418,21 +418,24 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   return SWIFT_OK;
 }
 
-typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const uint64_t *, const OptConsts);
+typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts);
+typedef void (*OptPackedKernel)(const ChunkDesc *, const uint64_t *, uint32_t, const OptConsts);
+
+#define SWIFT_PICK_KIND(KERNEL, U_, B_)                                                                        \
+  switch (kind) {                                                                                              \
+    case SWIFT_SGDM: return SWIFT_PICK_FLAGS(KERNEL, kSGDM, U_, B_);                                           \
+    case SWIFT_ADAM: return SWIFT_PICK_FLAGS(KERNEL, kADAM, U_, B_);                                           \
+    default: return SWIFT_PICK_FLAGS(KERNEL, kADAMW, U_, B_);                                                  \
+  }
+#define SWIFT_PICK_FLAGS(KERNEL, K, U_, B_)                                                                    \
+  (undo ? (bf16 ? SWIFT_PICK_XB(KERNEL, K, true, true, U_, B_) : SWIFT_PICK_XB(KERNEL, K, true, false, U_, B_)) \
+        : (bf16 ? SWIFT_PICK_XB(KERNEL, K, false, true, U_, B_) : SWIFT_PICK_XB(KERNEL, K, false, false, U_, B_)))
+#define SWIFT_PICK_XB(KERNEL, K, UNDO_, BF_, U_, B_) \
+  (xb ? KERNEL<K, UNDO_, BF_, true, U_, B_> : KERNEL<K, UNDO_, BF_, false, U_, B_>)
 
 template <int U, int BLOCK>
 OptKernel pick_kernel_shape(int kind, bool undo, bool bf16, bool xb) {
-#define SWIFT_PICK3(K, UNDO_, BF_) (xb ? opt_kernel<K, UNDO_, BF_, true, U, BLOCK> : opt_kernel<K, UNDO_, BF_, false, U, BLOCK>)
-#define SWIFT_PICK(K)                                                             \
-  (undo ? (bf16 ? SWIFT_PICK3(K, true, true) : SWIFT_PICK3(K, true, false))       \
-        : (bf16 ? SWIFT_PICK3(K, false, true) : SWIFT_PICK3(K, false, false)))
-  switch (kind) {
-    case SWIFT_SGDM: return SWIFT_PICK(kSGDM);
-    case SWIFT_ADAM: return SWIFT_PICK(kADAM);
-    default: return SWIFT_PICK(kADAMW);
-  }
-#undef SWIFT_PICK
-#undef SWIFT_PICK3
+  SWIFT_PICK_KIND(opt_kernel, U, BLOCK)
 }
 
 // The launch shapes that are compiled in.  Returns nullptr for any other (U, BLOCK).
@@ -442,6 +445,14 @@ OptKernel pick_kernel(const Tuning &t, int kind, bool undo, bool bf16, bool xb) 
 #undef SWIFT_SHAPE
   return nullptr;
 }
+
+// Device-mask launches always use the default shape.
+OptPackedKernel pick_packed_kernel(int kind, bool undo, bool bf16, bool xb) {
+  SWIFT_PICK_KIND(opt_packed_kernel, SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK)
+}
+#undef SWIFT_PICK_KIND
+#undef SWIFT_PICK_FLAGS
+#undef SWIFT_PICK_XB
 
 // Scratch of the device-mask calls: where each tensor's chunks sit, room for the packed table and
 // its slot count.  Calls that share a plan (the same tensors) share it, like the tensors themselves.
@@ -482,8 +493,10 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   SWIFT_HIP(hipGetDevice(&dev));
   DeviceInfo info;
   if ((rc = device_info(dev, &info))) return rc;
-  const Tuning tune = opt_tuning(hp->kind, hp->grad_dtype == SWIFT_BF16);
-  const OptKernel kernel = pick_kernel(tune, hp->kind, undo, hp->grad_dtype == SWIFT_BF16, l->param_bf16 != nullptr);
+  const bool bf16 = hp->grad_dtype == SWIFT_BF16, xb = l->param_bf16 != nullptr;
+  Tuning tune = opt_tuning(hp->kind, bf16);
+  if (want_dmask) tune.u = SWIFT_DEFAULT_U, tune.block = SWIFT_DEFAULT_BLOCK;     // the only packed-table shape
+  const OptKernel kernel = pick_kernel(tune, hp->kind, undo, bf16, xb);
   if (!kernel) return fail(SWIFT_EINVAL, "launch shape U=%d BLOCK=%d is not compiled in", tune.u, tune.block);
   const uint32_t tile_elems = (uint32_t)tune.u * (uint32_t)tune.block * 4u;
   if (want_dmask && (rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
@@ -495,30 +508,31 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   const uint64_t n_slots = (uint64_t)plan->n_chunks << tpc_shift;
   const hipStream_t stream = static_cast<hipStream_t>(stream_);
   const ChunkDesc *table = static_cast<const ChunkDesc *>(plan->chunks());
-  const uint64_t *n_slots_dev = nullptr;
-  uint64_t grid_cap = 0x7fffffffull;
-  if (want_dmask) {
-    // The host cannot size the grid to the marked tensors, and a workgroup that finds nothing to do
-    // still costs a dispatch (about 0.9 ns) plus the latency of the table fetch it needed to find
-    // that out.  So a small kernel first packs the chunk table by the mask, entirely on the device,
-    // and leaves the slot count beside it; the update kernel then runs over the packed table with a
-    // capped grid, strides, and stops at that count: every pass of its loop has a tile to process,
-    // and an almost empty mask costs at most the capped grid's idle dispatches.
-    if ((rc = packed_prepare(*plan))) return rc;
-    char *pm = static_cast<char *>(plan->packed_mem);
-    ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(pm + plan->packed_table_off);
-    uint64_t *count = reinterpret_cast<uint64_t *>(pm + plan->packed_count_off);
-    const long per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
-    if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
-    hipLaunchKernelGGL(compact_chunks_kernel, dim3((uint32_t)l->n), dim3(kThreads), 0, stream, table,
-                       reinterpret_cast<const TensorChunks *>(pm), (uint32_t)l->n, device_mask, tpc_shift, packed, count);
+  if (!want_dmask) {
+    hipLaunchKernelGGL(kernel, dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)), dim3((uint32_t)tune.block),
+                       lds_cap_bytes(info, tune), stream, table, n_slots, tpc_shift, c);
     SWIFT_HIP(hipGetLastError());
-    table = packed;
-    n_slots_dev = count;
+    return SWIFT_OK;
   }
-  const uint32_t grid = (uint32_t)std::min<uint64_t>(n_slots, grid_cap);
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3((uint32_t)tune.block), lds_cap_bytes(info, tune), stream, table, n_slots,
-                     tpc_shift, n_slots_dev, c);
+  // The host cannot size the grid to the marked tensors, and a workgroup that finds nothing to do
+  // still costs a dispatch (about 0.9 ns) plus the latency of the table fetch it needed to find that
+  // out.  So a small kernel first packs the chunk table by the mask, entirely on the device, and
+  // leaves the slot count beside it; the update kernel then runs over the packed table with a
+  // capped grid, strides, and stops at that count: every pass of its loop has a tile to process,
+  // and an almost empty mask costs at most the capped grid's idle dispatches.
+  if ((rc = packed_prepare(*plan))) return rc;
+  char *pm = static_cast<char *>(plan->packed_mem);
+  ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(pm + plan->packed_table_off);
+  uint64_t *count = reinterpret_cast<uint64_t *>(pm + plan->packed_count_off);
+  uint64_t grid_cap = 0x7fffffffull;
+  const long per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
+  if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
+  hipLaunchKernelGGL(compact_chunks_kernel, dim3((uint32_t)l->n), dim3(kThreads), 0, stream, table,
+                     reinterpret_cast<const TensorChunks *>(pm), (uint32_t)l->n, device_mask, tpc_shift, packed, count);
+  SWIFT_HIP(hipGetLastError());
+  hipLaunchKernelGGL(pick_packed_kernel(hp->kind, undo, bf16, xb), dim3((uint32_t)std::min<uint64_t>(n_slots, grid_cap)),
+                     dim3((uint32_t)tune.block), lds_cap_bytes(info, tune), stream, static_cast<const ChunkDesc *>(packed),
+                     static_cast<const uint64_t *>(count), tpc_shift, c);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }

@@ -48,9 +48,9 @@ opt_digest_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32
   uint64_t w = blockIdx.x;
   do {
     const uint64_t ci = w >> tpc_shift;
-    const ChunkDesc d = chunks[ci];
+    const ChunkDesc d = fetch_desc(chunks + ci);
     const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
-    if (ti * TILE >= d.len || d.x == nullptr) continue;
+    if (ti * TILE >= d.len) continue;
     OptDigestOp<KIND, UNDO> op{c, d.elem0};
     process_tile<OptDigestOp<KIND, UNDO>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
     const uint64_t sx = wave_sum_u64(op.dx), sm = wave_sum_u64(op.dm);

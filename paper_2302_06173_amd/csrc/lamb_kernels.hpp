@@ -91,9 +91,9 @@ lamb_moments_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint
   constexpr uint32_t TILE = U * BLOCK * 4u;
   uint64_t w = blockIdx.x;
   do {
-    const ChunkDesc d = chunks[w >> tpc_shift];
+    const ChunkDesc d = fetch_desc(chunks + (w >> tpc_shift));
     const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
-    if (ti * TILE >= d.len || d.x == nullptr) continue;          // slot past the end of a short chunk
+    if (ti * TILE >= d.len) continue;          // slot past the end of a short chunk
     LambMomentsOp op{c};
     process_tile<LambMomentsOp, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
     const double sx = wave_sum_f64(op.sx), su = wave_sum_f64(op.su);
@@ -138,9 +138,9 @@ lamb_apply_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32
   constexpr uint32_t TILE = U * BLOCK * 4u;
   uint64_t w = blockIdx.x;
   do {
-    const ChunkDesc d = chunks[w >> tpc_shift];
+    const ChunkDesc d = fetch_desc(chunks + (w >> tpc_shift));
     const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
-    if (ti * TILE >= d.len || d.x == nullptr) continue;
+    if (ti * TILE >= d.len) continue;
     LambApplyOp op{c, c.eta * lamb_ratio(norms, d.tensor)};
     process_tile<LambApplyOp, false, U, BLOCK>(op, d, ti, threadIdx.x);
   } while ((w += gridDim.x) < n_slots);
@@ -154,9 +154,9 @@ lamb_undo_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_
   constexpr uint32_t TILE = U * BLOCK * 4u;
   uint64_t w = blockIdx.x;
   do {
-    const ChunkDesc d = chunks[w >> tpc_shift];
+    const ChunkDesc d = fetch_desc(chunks + (w >> tpc_shift));
     const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
-    if (ti * TILE >= d.len || d.x == nullptr) continue;
+    if (ti * TILE >= d.len) continue;
     OptConsts cq = c;
     cq.eta = c.eta * lamb_ratio(norms, d.tensor);
     cq.inv_oml = 1.0 / (1.0 - cq.eta * c.lam);

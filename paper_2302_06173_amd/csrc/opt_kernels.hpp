@@ -290,41 +290,66 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
   }
 }
 
-// One workgroup per tile.  A chunk is up to chunk_elems consecutive elements of one tensor (the last
-// chunk of a tensor is short) and spans 2^tpc_shift tile slots, so slot w is tile (w & (tpc-1)) of
-// chunk (w >> tpc_shift).  The chunk table holds ready-made pointers, so a wavefront is one round
-// of scalar loads away from issuing its vector loads.  The grid normally equals the number of
-// slots: the hardware dispatcher then hands tiles out in address order as wavefronts retire, which
-// keeps the window of HBM pages in flight narrow (a persistent grid-stride loop lets workgroups
-// drift apart and measured 10-20 % slower for this 4-read/3-write pattern; so did several tiles
-// per workgroup).  The launch passes dynamic LDS that is never touched: it only caps how many
-// workgroups share a compute unit, because more than ~11 wavefronts per CU in flight lowers the
-// achieved HBM bandwidth of the mixed read/write stream.
-// `n_slots_dev` (nullable) is for launches whose slot count only the device knows (a table that
-// compact_chunks_kernel packed from a device-resident mask): the grid is then capped, workgroups
-// stride over the slots and stop at *n_slots_dev; entries of the table past that count are empty.
-template <int KIND, bool UNDO, bool BF16G, bool XB, int U, int BLOCK>
-__global__ void __launch_bounds__(BLOCK)
-opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_shift,
-           const uint64_t *__restrict__ n_slots_dev, const OptConsts c) {
+// A whole 64-byte table entry in one scalar load (the table is not written while a kernel that
+// reads it runs, which is what the constant address space requires).  Field by field the compiler
+// fetches the length first and the pointers in later rounds, each a scalar-cache round trip.
+__device__ __forceinline__ ChunkDesc fetch_desc(const ChunkDesc *p) {
+  typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+  typedef const __attribute__((address_space(4))) u32x16 *const_u32x16_ptr;
+  static_assert(sizeof(ChunkDesc) == sizeof(u32x16), "table entry is 64 bytes");
+  const u32x16 raw = *(const_u32x16_ptr)p;
+  ChunkDesc d;
+  __builtin_memcpy(&d, &raw, sizeof d);
+  return d;
+}
+
+// The tiles of one workgroup: slot w = blockIdx.x, then every gridDim.x-th slot below `end`.  A
+// chunk is up to chunk_elems consecutive elements of one tensor (the last chunk of a tensor is
+// short) and spans 2^tpc_shift tile slots, so slot w is tile (w & (tpc-1)) of chunk (w >> tpc_shift).
+// The chunk table holds ready-made pointers, so a wavefront is two rounds of scalar loads (kernel
+// arguments, table entry) away from issuing its vector loads; nothing else may sit in front of the
+// first entry fetch (one more dependent scalar load there cost the lightest kernel, SGDM with bf16
+// gradients, 7 %).  The host launches at most as many workgroups as the table has slots, so the
+// first pass needs no bounds test.
+template <int KIND, bool UNDO, bool BF16G, bool XB, int U, int BLOCK, bool DRAIN>
+__device__ __forceinline__ void opt_tiles(const ChunkDesc *__restrict__ chunks, uint64_t end, uint32_t tpc_shift,
+                                          const OptConsts &c) {
   constexpr uint32_t TILE = U * BLOCK * 4u;                      // elements per tile
   OptOp<KIND, UNDO, XB> op{c};
-  // The host launches at most n_slots workgroups (table entries, when the device holds the count),
-  // so the first pass needs no bounds test and no wait for the count before the entry is fetched.
-  typedef const __attribute__((address_space(4))) uint64_t *const_u64_ptr;   // uniform address: scalar load
-  const uint64_t end = n_slots_dev ? *(const_u64_ptr)n_slots_dev : n_slots;
   uint64_t w = blockIdx.x;
   do {
-    const ChunkDesc d = chunks[w >> tpc_shift];
+    const ChunkDesc d = fetch_desc(chunks + (w >> tpc_shift));
     const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
-    // (the pointer test is always true for a chunk with elements; it makes the compiler fetch the
-    //  whole entry with one round of scalar loads instead of the length first and the pointers later)
-    if (ti * TILE >= d.len || d.x == nullptr) continue;          // slot past the end of a short chunk
+    if (ti * TILE >= d.len) continue;                            // slot past the end of a short chunk
     process_tile<OptOp<KIND, UNDO, XB>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
     // A workgroup that goes round again first lets its stores drain (s_waitcnt vmcnt(0)), as a
     // retiring workgroup would before its slot is reused: measured 1-3 % faster for strided launches.
-    if (n_slots_dev) __builtin_amdgcn_s_waitcnt(0x0F70);
+    if constexpr (DRAIN) __builtin_amdgcn_s_waitcnt(0x0F70);
   } while ((w += gridDim.x) < end);
+}
+
+// One workgroup per tile: the grid equals the number of slots, and the hardware dispatcher hands
+// tiles out in address order as wavefronts retire, which keeps the window of HBM pages in flight
+// narrow (a persistent grid-stride loop lets workgroups drift apart and measured 10-20 % slower
+// for this 4-read/3-write pattern; so did several tiles per workgroup).  The launch passes dynamic
+// LDS that is never touched: it only caps how many workgroups share a compute unit, because more
+// than ~11 wavefronts per CU in flight lowers the achieved HBM bandwidth of the mixed read/write
+// stream.
+template <int KIND, bool UNDO, bool BF16G, bool XB, int U, int BLOCK>
+__global__ void __launch_bounds__(BLOCK)
+opt_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_shift, const OptConsts c) {
+  opt_tiles<KIND, UNDO, BF16G, XB, U, BLOCK, false>(chunks, n_slots, tpc_shift, c);
+}
+
+// The same update over a table that compact_chunks_kernel packed from a device-resident mask: only
+// the device knows how many slots it holds (*n_slots_dev; entries past that count are empty), so
+// the grid is capped by the host, workgroups stride over the slots and stop at the count.
+template <int KIND, bool UNDO, bool BF16G, bool XB, int U, int BLOCK>
+__global__ void __launch_bounds__(BLOCK)
+opt_packed_kernel(const ChunkDesc *__restrict__ chunks, const uint64_t *__restrict__ n_slots_dev, uint32_t tpc_shift,
+                  const OptConsts c) {
+  typedef const __attribute__((address_space(4))) uint64_t *const_u64_ptr;   // uniform address: scalar load
+  opt_tiles<KIND, UNDO, BF16G, XB, U, BLOCK, true>(chunks, *(const_u64_ptr)n_slots_dev, tpc_shift, c);
 }
 
 // Plain copy with the same launch shape (one tile of U*BLOCK 16-byte vectors per workgroup): the
