@@ -115,6 +115,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_adamw")
+    ap.add_argument("--layout", default="by_tensor", choices=["by_tensor", "by_stream"],
+                    help="where the state tensors are allocated: theta, g, m, v of a tensor side by side, "
+                         "or all theta, then all g, all m, all v (same values either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the launches reported under 'extras' (a profile of such a run holds the timed pass only)")
@@ -152,7 +155,7 @@ def main() -> int:
     N, n_t = w.n_params, len(w.shapes)
     log(f"[bench] workload {w.name}: {n_t} tensors, {N:,} params; drawing state on the GPU ...")
     t0 = time.perf_counter()
-    state = synth.make_state(w, "cuda:0", with_v=True)
+    state = synth.make_state(w, "cuda:0", with_v=True, layout=args.layout)
     torch.cuda.synchronize()
     log(f"[bench] state ready in {time.perf_counter() - t0:.1f} s; "
         f"{torch.cuda.memory_allocated() / 1e9:.1f} GB allocated")
@@ -295,7 +298,7 @@ def main() -> int:
         "config": {"workload": f"{w.name}: {n_t} tensors, {N} params, fp32 theta/m/v, "
                                f"{'bf16' if bf16 else 'fp32'} grads, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident",
                    "pass": "digest, masked AdamW step, digest, mask, selective undo, full AdamW/Adam/SGDM step+undo",
-                   "params_updated_or_undone_per_pass": params_per_pass,
+                   "params_updated_or_undone_per_pass": params_per_pass, "allocation_layout": args.layout,
                    "storage": "fp32 state, arithmetic in fp64 registers"},
         "roofline": {"bound": "hbm", "kernel": "opt_kernel<AdamW, undo>: mean of its 2 launches per pass "
                                                  "(selective undo of the marked tensors, full list)",

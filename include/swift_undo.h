@@ -56,6 +56,17 @@ typedef enum {
 
 typedef enum { SWIFT_F32 = 0, SWIFT_BF16 = 1 } swift_dtype; /* gradients only */
 
+/* Bits of swift_hparams.flags. */
+typedef enum {
+  SWIFT_CLAMP_V = 1 /* undo of Adam, AdamW and LAMB: a recovered second moment below zero is stored as
+                       +0.  "Undo Adam" (App. A) solves v_t = beta2 v_{t-1} + (1-beta2) g'^2 for
+                       v_{t-1}; since the step rounded v_t, the solution can come out slightly
+                       negative where v_{t-1} was almost zero, and a caller that does anything with
+                       v but re-apply step t with the same gradient would take the root of a negative
+                       number.  The paper applies no clamp, so this is off by default; the test
+                       v < 0 is made on the binary64 value, NaN stays NaN. */
+} swift_flags;
+
 /* Hyper-parameters in the paper's notation (Alg. 1, Alg. 2, App. A).  `step` is the t of m_t and
  * of the bias corrections 1 - beta^t; a step and the undo of that step use the same value. */
 typedef struct {
@@ -68,6 +79,8 @@ typedef struct {
   double dampening;     /* tau in [0, 1]  (SGDM) */
   double beta1, beta2;  /* in [0, 1)      (Adam, AdamW) */
   double eps;           /* >= 0           (Adam, AdamW) */
+  int32_t flags;        /* swift_flags, 0 for the paper's algorithms as printed */
+  int32_t reserved;     /* must be 0 */
 } swift_hparams;
 
 /* A list of n tensors.  All arrays are HOST arrays of length n; the pointers they hold are

@@ -63,6 +63,8 @@ def _load():
         lib.oracle_lamb_step.argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p, p]
         lib.oracle_lamb_undo.argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p, p]
         lib.oracle_lamb_step.restype = lib.oracle_lamb_undo.restype = None
+        lib.oracle_clamp_v.argtypes = [i64, p]
+        lib.oracle_clamp_v.restype = None
         lib.oracle_bf16_round.argtypes = [i64, p, p]
         lib.oracle_bf16_round.restype = None
         lib.oracle_digest.argtypes = [p, i64]
@@ -83,6 +85,7 @@ class Hyper:
     beta2: float = 0.999
     eps: float = 1e-8
     t: int = 1                # index of the update applied / undone
+    clamp_v: bool = False     # undo only, not in the paper: a recovered v below zero becomes +0
 
 
 def widen(a) -> np.ndarray:
@@ -141,7 +144,10 @@ def opt_undo(hp: Hyper, x_new, g, m_new, v_new=None):
         raise ZeroDivisionError("undo: beta = 0 is not invertible")
     if hp.kind == ADAMW and 1.0 - hp.eta * hp.lam == 0.0:
         raise ZeroDivisionError("undo: eta*lambda = 1 is not invertible")
-    return _run("undo", hp, x_new, g, m_new, v_new)
+    x_old, m_old, v_old = _run("undo", hp, x_new, g, m_new, v_new)
+    if hp.clamp_v and v_old is not None:
+        _load().oracle_clamp_v(v_old.size, _ptr(v_old))
+    return x_old, m_old, v_old
 
 
 def lamb_step(hp: Hyper, x, g, m, v):
@@ -171,6 +177,8 @@ def lamb_undo(hp: Hyper, x_new, g, m_new, v_new, norms):
     xo, mo, vo = np.empty(n), np.empty(n), np.empty(n)
     lib.oracle_lamb_undo(n, _ptr(x), _ptr(g), _ptr(m), _ptr(v), hp.eta, hp.lam, hp.beta1, hp.beta2, hp.eps,
                          int(hp.t), _ptr(norms), _ptr(xo), _ptr(mo), _ptr(vo))
+    if hp.clamp_v:
+        lib.oracle_clamp_v(n, _ptr(vo))
     return xo, mo, vo
 
 

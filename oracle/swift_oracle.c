@@ -199,6 +199,18 @@ void oracle_lamb_undo(int64_t n, const double *x_new, const double *g, const dou
 }
 
 /* ------------------------------------------------------------------------- */
+/* Not in the paper: optional clamp of the second moment an undo recovered.     */
+/* "Undo Adam" (App. A) solves v_t = beta2 v_{t-1} + (1-beta2) g'^2 for v_{t-1};  */
+/* with a rounded v_t the solution can be slightly negative.  The clamp is a     */
+/* separate pass over the undo's output: values below zero become +0, NaN stays. */
+void oracle_clamp_v(int64_t n, double *v_old)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        if (v_old[i] < 0.0) v_old[i] = 0.0;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* bfloat16 copy of binary32 parameters (mixed-precision training keeps one next to   */
 /* the fp32 master weights; not in the paper).  bfloat16 is the upper half of binary32 */
 /* (8 exponent bits, 7 fraction bits); the copy is the nearest bfloat16, ties to the   */

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libswift_undo.so")
 SWIFT_OK, SWIFT_EINVAL, SWIFT_ENOTINVERTIBLE, SWIFT_EHIP = 0, -1, -2, -3
 SWIFT_SGDM, SWIFT_ADAM, SWIFT_ADAMW, SWIFT_LAMB = 0, 1, 2, 3
 SWIFT_F32, SWIFT_BF16 = 0, 1
+SWIFT_CLAMP_V = 1
 KINDS = {"sgdm": SWIFT_SGDM, "adam": SWIFT_ADAM, "adamw": SWIFT_ADAMW, "lamb": SWIFT_LAMB}
 
 if not os.path.exists(LIB_PATH):
@@ -31,7 +32,7 @@ class SwiftHparams(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("grad_dtype", ctypes.c_int32), ("step", ctypes.c_int64),
                 ("lr", ctypes.c_double), ("weight_decay", ctypes.c_double), ("momentum", ctypes.c_double),
                 ("dampening", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
-                ("eps", ctypes.c_double)]
+                ("eps", ctypes.c_double), ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class SwiftTensorList(ctypes.Structure):
@@ -105,10 +106,11 @@ def _stream_handle(stream) -> Optional[int]:
 
 def hparams(kind, step: int, lr: float, weight_decay: float = 0.0, momentum: float = 0.0,
             dampening: float = 0.0, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
-            grad_bf16: bool = False) -> SwiftHparams:
+            grad_bf16: bool = False, clamp_v: bool = False) -> SwiftHparams:
     k = KINDS[kind] if isinstance(kind, str) else int(kind)
     return SwiftHparams(k, SWIFT_BF16 if grad_bf16 else SWIFT_F32, int(step), float(lr), float(weight_decay),
-                        float(momentum), float(dampening), float(beta1), float(beta2), float(eps))
+                        float(momentum), float(dampening), float(beta1), float(beta2), float(eps),
+                        SWIFT_CLAMP_V if clamp_v else 0, 0)
 
 
 def _ptr_array(tensors: Sequence[torch.Tensor]):

@@ -199,7 +199,7 @@ Tuning opt_tuning(int kind, bool bf16) {
   // Measured optima: the fewer bytes a wavefront moves (SGDM has 3 streams in and 2 out instead of
   // 4 and 3; bf16 gradients halve one stream), the more wavefronts a compute unit wants.
   const int waves = kind == SWIFT_SGDM ? (bf16 ? SWIFT_DEFAULT_WAVES_PER_CU_SGDM + 1 : SWIFT_DEFAULT_WAVES_PER_CU_SGDM)
-                                       : (bf16 ? SWIFT_DEFAULT_WAVES_PER_CU + 2 : SWIFT_DEFAULT_WAVES_PER_CU);
+                                       : (bf16 ? SWIFT_DEFAULT_WAVES_PER_CU + 1 : SWIFT_DEFAULT_WAVES_PER_CU);
   Tuning t{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK, waves};
   t.u = (int)env_long("SWIFT_TILE_U", t.u);
   t.block = (int)env_long("SWIFT_TILE_BLOCK", t.block);
@@ -256,7 +256,10 @@ int validate_hparams(const swift_hparams *hp, bool undo, OptConsts *c) {
   if (hp->step < 1) return fail(SWIFT_EINVAL, "step must be >= 1 (got %lld)", (long long)hp->step);
   if (!std::isfinite(hp->lr)) return fail(SWIFT_EINVAL, "lr is not finite");
   if (!std::isfinite(hp->weight_decay) || hp->weight_decay < 0) return fail(SWIFT_EINVAL, "weight_decay must be finite and >= 0");
+  if ((hp->flags & ~(int32_t)SWIFT_CLAMP_V) != 0 || hp->reserved != 0)
+    return fail(SWIFT_EINVAL, "unknown flag bits 0x%x (reserved = %d)", (unsigned)hp->flags, hp->reserved);
   memset(c, 0, sizeof *c);
+  c->clamp_v = (hp->flags & SWIFT_CLAMP_V) ? 1 : 0;
   c->eta = hp->lr;
   c->lam = hp->weight_decay;
   if (hp->kind == SWIFT_SGDM) {

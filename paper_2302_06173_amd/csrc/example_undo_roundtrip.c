@@ -45,7 +45,7 @@ int main(void) {
     for (int k = 0; k < 3; ++k) { state[k * NT + t] = d[t][k == 0 ? 0 : k + 1]; state_numel[k * NT + t] = numel[t]; }
   }
   const swift_tensor_list list = {NT, param, grad, m, v, numel, NULL};
-  const swift_hparams hp = {SWIFT_ADAMW, SWIFT_F32, 100, 6e-4, 0.1, 0.0, 0.0, 0.9, 0.95, 1e-8};
+  const swift_hparams hp = {SWIFT_ADAMW, SWIFT_F32, 100, 6e-4, 0.1, 0.0, 0.0, 0.9, 0.95, 1e-8, 0, 0};
   const uint8_t only_first[NT] = {1, 0};     /* the update reached tensor 0 before the failure */
   uint64_t *dig0, *dig1;
   uint8_t *dmask, hmask[NT];

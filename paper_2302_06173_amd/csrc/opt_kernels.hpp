@@ -71,7 +71,7 @@ struct OptConsts {
   double eps;
   double inv_oml;                         // 1/(1 - eta*lambda)   (AdamW undo)
   int32_t mu_is_zero;
-  int32_t pad;
+  int32_t clamp_v;                        // undo: store a recovered v below zero as +0
 };
 
 // Tensor pointers come out of a descriptor table, so the compiler cannot tell their address
@@ -159,7 +159,9 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
       const double gp = (KIND == kADAM) ? fma(c.lam, xt, g) : g;
       xf = (float)xt;
       mf = (float)(fma(-c.c1, gp, m) * c.inv_b1);
-      vf = (float)(fma(-c.c2, gp * gp, v) * c.inv_b2);
+      double vt = fma(-c.c2, gp * gp, v) * c.inv_b2;
+      if (c.clamp_v && vt < 0.0) vt = 0.0;          // optional, not in the paper: see SWIFT_CLAMP_V
+      vf = (float)vt;
     }
   }
 }

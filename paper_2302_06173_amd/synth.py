@@ -74,6 +74,19 @@ def llama7b_shapes() -> List[Shape]:
     return out
 
 
+def vit_128_32_shapes() -> List[Shape]:
+    """ViT-Large/32 deepened from 24 to 128 transformer layers, hidden size unchanged (the paper's
+    ViT-128/32, section "Experimental setup"), 224x224 input, 1000 classes: 1,544 tensors,
+    1,616,542,696 parameters (the paper's table says 1.64 B; the text does not give the head or
+    the input size, the difference is about 1 %)."""
+    h, f, patch, tokens = 1024, 4096, 32, (224 // 32) ** 2 + 1
+    out: List[Shape] = [(1, 1, h), (1, tokens, h), (h, 3, patch, patch), (h,)]
+    for _ in range(128):
+        out += [(h,), (h,), (3 * h, h), (3 * h,), (h, h), (h,), (h,), (h,), (f, h), (f,), (h, f), (h,)]
+    out += [(h,), (h,), (1000, h), (1000,)]
+    return out
+
+
 @dataclass
 class Workload:
     """One benchmark / parity configuration: shapes, value recipe and hyper-parameters."""
@@ -103,7 +116,7 @@ _ADAM = dict(lr=1e-3, weight_decay=0.0, beta1=0.9, beta2=0.999, eps=1e-8)
 
 
 def workloads() -> dict:
-    """The five configurations, smallest first."""
+    """The five benchmark configurations, smallest first, then the additional SGD-momentum list."""
     return {
         "sgdm_flat_1m": Workload(
             "sgdm_flat_1m", [(1 << 20,)], "sgdm",
@@ -121,6 +134,11 @@ def workloads() -> dict:
             "llama7b_adamw", llama7b_shapes(), "adamw",
             dict(lr=6e-4, weight_decay=0.1, beta1=0.9, beta2=0.95, eps=1e-8, step=100000), seed=5,
             zero_frac=0.10, outlier_frac=0.01, masked_fraction=0.5),
+        # beyond the five: the paper trains its ViT-128/32 (and Wide-ResNet-50) with SGD-momentum
+        "vit_128_32_sgdm": Workload(
+            "vit_128_32_sgdm", vit_128_32_shapes(), "sgdm",
+            dict(lr=0.1, momentum=0.9, dampening=0.0, weight_decay=1e-4, step=1), seed=6, std_m=1e-3,
+            masked_fraction=0.5),
     }
 
 
@@ -137,33 +155,54 @@ class State:
         return State(c(self.theta), c(self.grad), c(self.m), c(self.v))
 
 
-def make_state(w: Workload, device, shapes: Optional[Sequence[Shape]] = None, with_v: Optional[bool] = None) -> State:
-    """Draw the workload's state on `device` (same seed and device type => same bits)."""
+def make_state(w: Workload, device, shapes: Optional[Sequence[Shape]] = None, with_v: Optional[bool] = None,
+               layout: str = "by_tensor") -> State:
+    """Draw the workload's state on `device` (same seed and device type => same bits, whatever the
+    layout).
+
+    layout says where the tensors are allocated, not what they hold.  "by_tensor" (default): theta,
+    g, m, v of one tensor next to each other, tensor after tensor.  "by_stream": every theta, then
+    every gradient, then every m, then every v.  Achieved HBM bandwidth depends on where the four
+    streams lie relative to each other (a few per cent either way, by workload), so benchmarks
+    state the layout they used."""
     shapes = list(w.shapes if shapes is None else shapes)
     with_v = (w.kind != "sgdm") if with_v is None else with_v
+    if layout not in ("by_stream", "by_tensor"):
+        raise ValueError(f"unknown layout {layout!r}")
     dev = torch.device(device)
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
-    th, gr, mo, vo = [], [], [], []
-    for shp in shapes:
-        n = numel(shp)
-        x = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_theta, generator=gen)
-        g = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_grad, generator=gen)
-        m = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_m, generator=gen)
+    gdt = torch.bfloat16 if w.grad_bf16 else torch.float32
+    sizes = [numel(shp) for shp in shapes]
+    new = lambda n, dt=torch.float32: torch.empty(n, dtype=dt, device=dev)
+    if layout == "by_stream":
+        th = [new(n) for n in sizes]
+        gr = [new(n, gdt) for n in sizes]
+        mo = [new(n) for n in sizes]
+        vo = [new(n) for n in sizes] if with_v else None
+    else:
+        th, gr, mo, vo = [], [], [], ([] if with_v else None)
+        for n in sizes:
+            th.append(new(n))
+            gr.append(new(n, gdt))
+            mo.append(new(n))
+            if with_v:
+                vo.append(new(n))
+    for i, n in enumerate(sizes):                      # draw order: theta, g, m, v, selector; tensor by tensor
+        th[i].normal_(0.0, w.std_theta, generator=gen)
+        g = new(n).normal_(0.0, w.std_grad, generator=gen) if w.grad_bf16 else gr[i].normal_(0.0, w.std_grad, generator=gen)
+        mo[i].normal_(0.0, w.std_m, generator=gen)
         if with_v:
-            v = torch.empty(n, dtype=torch.float32, device=dev).normal_(0.0, w.std_v, generator=gen).abs_()
-            vo.append(v)
+            vo[i].normal_(0.0, w.std_v, generator=gen).abs_()
         if w.zero_frac > 0 or w.outlier_frac > 0:
-            r = torch.empty(n, dtype=torch.float32, device=dev).uniform_(0.0, 1.0, generator=gen)
+            r = new(n).uniform_(0.0, 1.0, generator=gen)
             g[r < w.zero_frac] = 0.0
             g[r >= 1.0 - w.outlier_frac] *= w.outlier_scale
             del r
         if w.grad_bf16:
-            g = g.to(torch.bfloat16)      # round to nearest even; the kernels widen it back exactly
-        th.append(x)
-        gr.append(g)
-        mo.append(m)
-    return State(th, gr, mo, vo if with_v else None)
+            gr[i].copy_(g)                # round to nearest even; the kernels widen it back exactly
+        del g
+    return State(th, gr, mo, vo)
 
 
 def tensor_mask(w: Workload, n_tensors: int) -> List[int]:

@@ -19,14 +19,14 @@ def to_np(t: torch.Tensor) -> np.ndarray:
 def oracle_hyper(kind: str, hp: dict) -> oracle.Hyper:
     return oracle.Hyper(kind=kind, eta=hp["lr"], lam=hp.get("weight_decay", 0.0), mu=hp.get("momentum", 0.0),
                         tau=hp.get("dampening", 0.0), beta1=hp.get("beta1", 0.9), beta2=hp.get("beta2", 0.999),
-                        eps=hp.get("eps", 1e-8), t=hp.get("step", 1))
+                        eps=hp.get("eps", 1e-8), t=hp.get("step", 1), clamp_v=bool(hp.get("clamp_v", False)))
 
 
 def binding_hparams(B, kind: str, hp: dict, grad_bf16: bool = False):
     return B.hparams(kind, step=hp.get("step", 1), lr=hp["lr"], weight_decay=hp.get("weight_decay", 0.0),
                      momentum=hp.get("momentum", 0.0), dampening=hp.get("dampening", 0.0),
                      beta1=hp.get("beta1", 0.9), beta2=hp.get("beta2", 0.999), eps=hp.get("eps", 1e-8),
-                     grad_bf16=grad_bf16)
+                     grad_bf16=grad_bf16, clamp_v=bool(hp.get("clamp_v", False)))
 
 
 def assert_parity(gpu32: np.ndarray, ref64: np.ndarray, what: str, scale: float = None):

@@ -28,9 +28,9 @@ def test_every_declared_symbol_is_exported(B):
 
 def test_struct_layouts_match_the_header(B):
     # int32, int32, int64, 7 doubles / int64 + 5 pointers: no padding surprises
-    assert ctypes.sizeof(B.SwiftHparams) == 4 + 4 + 8 + 7 * 8
+    assert ctypes.sizeof(B.SwiftHparams) == 4 + 4 + 8 + 7 * 8 + 4 + 4
     assert ctypes.sizeof(B.SwiftTensorList) == 8 + 6 * 8
-    assert B.SwiftHparams.lr.offset == 16 and B.SwiftHparams.eps.offset == 64
+    assert B.SwiftHparams.lr.offset == 16 and B.SwiftHparams.eps.offset == 64 and B.SwiftHparams.flags.offset == 72
 
 
 def test_digest_count_is_host_arithmetic(B):
@@ -76,6 +76,13 @@ def test_hyper_parameter_domain(B, fn):
         assert B.swift_last_error() != ""
     hp = B.hparams("adam", step=1, lr=0.1)
     hp.grad_dtype = 9
+    assert _call(B, fn, hp) == B.SWIFT_EINVAL
+    assert _call(B, fn, B.hparams("adam", step=1, lr=0.1, clamp_v=True)) == B.SWIFT_OK
+    hp = B.hparams("adam", step=1, lr=0.1)
+    hp.flags = 2                                                # a bit nobody defined
+    assert _call(B, fn, hp) == B.SWIFT_EINVAL and "flag" in B.swift_last_error()
+    hp = B.hparams("adam", step=1, lr=0.1)
+    hp.reserved = 1
     assert _call(B, fn, hp) == B.SWIFT_EINVAL
 
 
@@ -145,6 +152,7 @@ def test_synthetic_workloads_have_the_stated_sizes():
         "bert_large_adamw": (391, 335_141_888),
         "gpt2_xl_adamw_bf16g": (580, 1_557_611_200),
         "llama7b_adamw": (291, 6_738_415_616),
+        "vit_128_32_sgdm": (1544, 1_616_542_696),
     }
     # seeded: same seed, same bits; the mask picks the stated fraction
     s1 = synth.make_state(w["sgdm_flat_1m"], "cpu", shapes=[(33,), (5,)])

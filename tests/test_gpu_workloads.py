@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's real shapes: the five synthetic workloads, launched exactly as
+"""GPU parity at the benchmark's real shapes: the five synthetic workloads and the additional SGD-momentum list, launched exactly as
 bench.py launches them (same binding calls, default launch shape).
 
 Small workloads are compared with the fp64 oracle element by element over every tensor.  For the
@@ -144,6 +144,9 @@ def _selective_flow(B, synth, w, every):
     s = synth.make_state(w, "cuda")
     tl = B.TensorList(s.theta, s.grad, s.m, s.v)
     hp = binding_hparams(B, w.kind, w.hyper, w.grad_bf16)
+    state_lists = [s.theta, s.m] + ([s.v] if s.v is not None else [])
+    ng = len(state_lists)                                          # digest rows that a step changes
+    written = (0, 2, 3)[:ng]                                       # their positions in a _grab tuple
     frac = w.masked_fraction or 0.5
     mask = synth.tensor_mask(synth.Workload(**{**w.__dict__, "masked_fraction": frac}), n_t)
     picks = _sample_ranges(w.shapes, synth, every)
@@ -152,18 +155,18 @@ def _selective_flow(B, synth, w, every):
     assert on and off
     # gradients are digested too (as 32-bit words; bf16 tensors have an even element count here)
     gwords = [g.view(torch.int32) if g.dtype == torch.bfloat16 else g for g in s.grad]
-    bufs = B.BufferList(s.theta + s.m + s.v + gwords)
+    bufs = B.BufferList(sum(state_lists, []) + gwords)
     orig = _grab(s, picks)
     d0 = B.swift_state_digest(bufs, 0)
     B.swift_opt_step(tl, hp, host_mask=mask)                       # the interrupted update
     d1 = B.swift_state_digest(bufs, 0)
-    dmask = B.swift_mask_from_digests(d0[:3 * n_t], d1[:3 * n_t], n_t)
+    dmask = B.swift_mask_from_digests(d0[:ng * n_t], d1[:ng * n_t], n_t)
     torch.cuda.synchronize()
     mid = _grab(s, picks)
-    a, b = digests_np(d0).reshape(4, n_t), digests_np(d1).reshape(4, n_t)
-    assert np.array_equal(a[3], b[3]), "a gradient changed"
-    changed = (a[:3] != b[:3])
-    assert np.array_equal(changed.all(axis=0), np.array(mask, bool)), "theta, m and v of exactly the marked tensors change"
+    a, b = digests_np(d0).reshape(ng + 1, n_t), digests_np(d1).reshape(ng + 1, n_t)
+    assert np.array_equal(a[ng], b[ng]), "a gradient changed"
+    changed = (a[:ng] != b[:ng])
+    assert np.array_equal(changed.all(axis=0), np.array(mask, bool)), "theta, m (and v) of exactly the marked tensors change"
     assert np.array_equal(dmask.cpu().numpy(), np.array(mask, np.uint8))
     # the oracle's hash of the sampled whole tensors agrees with the device digests
     for (i, lo, hi) in picks:
@@ -172,20 +175,20 @@ def _selective_flow(B, synth, w, every):
             assert b[1][i] == oracle.digest(mid[(i, lo, hi)][2])[0]
     _check_slices(w.kind, w.hyper, {k: orig[k] for k in on}, {k: mid[k] for k in on}, False, f"{w.name} masked step")
     for k in off:
-        for j in (0, 2, 3):
+        for j in written:
             assert np.array_equal(orig[k][j].view(np.uint32), mid[k][j].view(np.uint32)), f"unmarked {k} changed"
     del orig
     B.swift_opt_undo_dmask(tl, hp, dmask)                          # selective undo, mask stays on the device
     d2 = B.swift_state_digest(bufs, 0)
     torch.cuda.synchronize()
     end = _grab(s, picks)
-    c = digests_np(d2).reshape(4, n_t)
-    assert np.array_equal(c[3], a[3])
+    c = digests_np(d2).reshape(ng + 1, n_t)
+    assert np.array_equal(c[ng], a[ng])
     off_idx = ~np.array(mask, bool)
-    assert np.array_equal(c[:3, off_idx], a[:3, off_idx]), "an unmarked tensor changed during undo"
+    assert np.array_equal(c[:ng, off_idx], a[:ng, off_idx]), "an unmarked tensor changed during undo"
     _check_slices(w.kind, w.hyper, {k: mid[k] for k in on}, {k: end[k] for k in on}, True, f"{w.name} selective undo")
     for k in off:
-        for j in (0, 2, 3):
+        for j in written:
             assert np.array_equal(mid[k][j].view(np.uint32), end[k][j].view(np.uint32))
     # and one full-list step + undo in the launch configuration the benchmark times
     B.swift_opt_step(tl, hp)
@@ -200,6 +203,11 @@ def _selective_flow(B, synth, w, every):
 def test_gpt2_xl_bf16_gradients_sampled(B, synth):
     """Configuration 4 (1.56 B parameters, bf16 gradients widened in the kernel)."""
     _selective_flow(B, synth, synth.workloads()["gpt2_xl_adamw_bf16g"], every=97)
+
+
+def test_vit_128_32_sgdm_sampled(B, synth):
+    """The additional SGD-momentum list (1.62 B parameters, 1,544 tensors; theta, g, m only)."""
+    _selective_flow(B, synth, synth.workloads()["vit_128_32_sgdm"], every=131)
 
 
 def test_llama7b_selective_undo_sampled(B, synth):

@@ -509,3 +509,43 @@ def test_bf16_round_matches_torch_and_the_definition():
     tie = np.array([1.00390625, 1.01171875], dtype=np.float32)    # halfway between neighbours: 0x3F80|0x3F81 and 0x3F81|0x3F82
     assert oracle.bf16_round(tie).tolist() == [0x3F80, 0x3F82]
     assert oracle.bf16_round(np.array([3.4028235e38], np.float32))[0] == 0x7F80   # rounds up to infinity
+
+
+# ------------------------------------------------------------------------------------------
+# Optional clamp of the recovered second moment (not in the paper; off by default).
+def test_v_clamp_only_touches_negative_values():
+    rng = np.random.default_rng(77)
+    n = 4000
+    x = rng.normal(0, 0.02, n)
+    g = rng.normal(0, 1e-3, n)
+    m = rng.normal(0, 1e-4, n)
+    v = np.abs(rng.normal(0, 1e-6, n))
+    v[::7] = 0.0                                                  # where the step leaves (1-beta2) g^2 only
+    for kind in ("adam", "adamw"):
+        h = oracle.Hyper(kind, eta=1e-3, lam=0.01, beta1=0.9, beta2=0.999, eps=1e-8, t=10)
+        x1, m1, v1 = oracle.opt_step(h, x, g, m, v)
+        v1 = v1.astype(np.float32)                                # the stored state is binary32: rounding can push
+        xa, ma, va = oracle.opt_undo(h, x1, g, m1, v1)            # the recovered v below zero
+        hc = oracle.Hyper(kind, eta=1e-3, lam=0.01, beta1=0.9, beta2=0.999, eps=1e-8, t=10, clamp_v=True)
+        xb, mb, vb = oracle.opt_undo(hc, x1, g, m1, v1)
+        assert (va < 0).any(), "the case must exercise the clamp"
+        assert np.array_equal(xa, xb) and np.array_equal(ma, mb)
+        assert np.array_equal(vb, np.where(va < 0, 0.0, va))      # the definition, written out
+        assert (vb >= 0).all() and not np.signbit(vb[va < 0]).any()
+        # the default stays the paper's formula
+        assert np.array_equal(va, (v1.astype(np.float64) - (1 - h.beta2) * (g + (h.lam * xa if kind == "adam" else 0)) ** 2) / h.beta2)
+
+
+def test_v_clamp_keeps_nan_and_applies_to_lamb():
+    h = oracle.Hyper("adamw", eta=1e-3, lam=0.0, beta1=0.5, beta2=0.5, eps=1e-8, t=1, clamp_v=True)
+    x = np.array([1.0, 1.0, 1.0]); g = np.array([2.0, 0.0, 1.0]); m = np.array([0.0, 0.0, 0.0])
+    v_new = np.array([1.0, np.nan, 3.0])                          # (1 - 0.5*4)/0.5 = -2 -> 0;  NaN;  (3 - 0.5)/0.5 = 5
+    _, _, v_old = oracle.opt_undo(h, x, g, m, v_new)
+    assert v_old[0] == 0.0 and np.isnan(v_old[1]) and v_old[2] == 5.0
+    norms = np.array([1.0, 1.0])
+    _, _, vl = oracle.lamb_undo(h, x, g, m, np.array([1.0, 1.0, 3.0]), norms)
+    assert vl[0] == 0.0 and vl[1] == 2.0 and vl[2] == 5.0
+    h.clamp_v = False
+    _, _, vl = oracle.lamb_undo(h, x, g, m, np.array([1.0, 1.0, 3.0]), norms)
+    assert vl[0] == -2.0
+
