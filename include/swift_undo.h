@@ -95,7 +95,7 @@ typedef struct {
  * swift_opt_undo (host- and device-mask forms) also write, for every tensor they touch, the bfloat16
  * nearest to each new binary32 parameter (ties to even, NaN -> 0x7FC0) into param_bf16[i] (2-byte
  * aligned, numel[i] elements, write only): 2 more bytes of traffic per parameter instead of a cast pass.
- * The LAMB and fused-digest entry points do not take it (SWIFT_EINVAL). */
+ * So do the LAMB and fused-digest entry points (the digests cover theta, m and v, not the copy). */
 typedef struct {
   int64_t n;
   void *const *param;

@@ -555,11 +555,11 @@ LambMomentsKernel pick_lamb_moments(int u, bool bf16) {
   }
 }
 
-LambApplyKernel pick_lamb_apply(int u) {
+LambApplyKernel pick_lamb_apply(int u, bool xb) {
   switch (u) {
-    case 1: return lamb_apply_kernel<1, 64>;
-    case 2: return lamb_apply_kernel<2, 64>;
-    default: return lamb_apply_kernel<4, 64>;
+    case 1: return xb ? lamb_apply_kernel<true, 1, 64> : lamb_apply_kernel<false, 1, 64>;
+    case 2: return xb ? lamb_apply_kernel<true, 2, 64> : lamb_apply_kernel<false, 2, 64>;
+    default: return xb ? lamb_apply_kernel<true, 4, 64> : lamb_apply_kernel<false, 4, 64>;
   }
 }
 
@@ -607,7 +607,6 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
   int rc = validate_hparams(hp, undo, &c);
   if (rc) return rc;
   if (hp->kind != SWIFT_LAMB) return fail(SWIFT_EINVAL, "swift_lamb_* needs kind = SWIFT_LAMB");
-  if (l && l->param_bf16) return fail(SWIFT_EINVAL, "swift_lamb_* does not write a bfloat16 parameter copy");
   if ((rc = validate_list(l, hp))) return rc;
   if (l->n == 0) return SWIFT_OK;
   if (!norms) return fail(SWIFT_EINVAL, "norms_device is NULL");
@@ -617,7 +616,7 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
   DeviceInfo info;
   if ((rc = device_info(dev, &info))) return rc;
   if ((rc = check_device_range(norms, (size_t)l->n * 16, dev, "norms_device", 0))) return rc;
-  const bool bf16 = hp->grad_dtype == SWIFT_BF16;
+  const bool bf16 = hp->grad_dtype == SWIFT_BF16, xb = l->param_bf16 != nullptr;
   std::shared_ptr<Plan> plan;
   if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -633,7 +632,8 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
   const ChunkDesc *chunks = static_cast<const ChunkDesc *>(plan->chunks());
   if (undo) {
     if (plan->n_chunks == 0) return SWIFT_OK;
-    const auto k = bf16 ? lamb_undo_kernel<true, 1, 64> : lamb_undo_kernel<false, 1, 64>;
+    const auto k = bf16 ? (xb ? lamb_undo_kernel<true, true, 1, 64> : lamb_undo_kernel<true, false, 1, 64>)
+                        : (xb ? lamb_undo_kernel<false, true, 1, 64> : lamb_undo_kernel<false, false, 1, 64>);
     hipLaunchKernelGGL(k, dim3((uint32_t)std::min<uint64_t>(slotsu, 0x7fffffffull)), dim3(64), lds_cap_bytes(info, tu),
                        stream, chunks, slotsu, su, c, static_cast<const double *>(norms));
     SWIFT_HIP(hipGetLastError());
@@ -649,7 +649,7 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
                      static_cast<const TensorSpan *>(plan->lamb_spans), static_cast<const double2 *>(plan->lamb_partial), norms);
   SWIFT_HIP(hipGetLastError());
   if (plan->n_chunks) {
-    hipLaunchKernelGGL(pick_lamb_apply(u3), dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64),
+    hipLaunchKernelGGL(pick_lamb_apply(u3, xb), dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64),
                        lds_cap_bytes(info, t3), stream, chunks, slots3, s3, c, static_cast<const double *>(norms));
     SWIFT_HIP(hipGetLastError());
   }
@@ -683,16 +683,18 @@ int fused_prepare(Plan &plan) {
 
 typedef void (*FusedKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts, unsigned long long *);
 
-FusedKernel pick_fused(int kind, bool undo, bool bf16) {
-#define SWIFT_PICK(K)                                                                                       \
-  (undo ? (bf16 ? opt_digest_kernel<K, true, true, 1, 64> : opt_digest_kernel<K, true, false, 1, 64>)       \
-        : (bf16 ? opt_digest_kernel<K, false, true, 1, 64> : opt_digest_kernel<K, false, false, 1, 64>))
+FusedKernel pick_fused(int kind, bool undo, bool bf16, bool xb) {
+#define SWIFT_PICK2(K, UNDO_, BF_) (xb ? opt_digest_kernel<K, UNDO_, BF_, true, 1, 64> : opt_digest_kernel<K, UNDO_, BF_, false, 1, 64>)
+#define SWIFT_PICK(K)                                                         \
+  (undo ? (bf16 ? SWIFT_PICK2(K, true, true) : SWIFT_PICK2(K, true, false))   \
+        : (bf16 ? SWIFT_PICK2(K, false, true) : SWIFT_PICK2(K, false, false)))
   switch (kind) {
     case SWIFT_SGDM: return SWIFT_PICK(kSGDM);
     case SWIFT_ADAM: return SWIFT_PICK(kADAM);
     default: return SWIFT_PICK(kADAMW);
   }
 #undef SWIFT_PICK
+#undef SWIFT_PICK2
 }
 
 int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, uint64_t *digests,
@@ -701,7 +703,6 @@ int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_
   int rc = validate_hparams(hp, undo, &c);
   if (rc) return rc;
   if (hp->kind == SWIFT_LAMB) return fail(SWIFT_EINVAL, "the fused digest entry points do not take LAMB");
-  if (l && l->param_bf16) return fail(SWIFT_EINVAL, "the fused digest entry points do not write a bfloat16 parameter copy");
   if ((rc = validate_list(l, hp))) return rc;
   if (l->n == 0) return SWIFT_OK;
   for (int64_t i = 0; i < l->n; ++i)
@@ -733,7 +734,7 @@ int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_
     SWIFT_HIP(hipGetLastError());
     const uint32_t shift = shift_for(256u, plan->chunk_elems);
     const uint64_t n_slots = (uint64_t)plan->n_chunks << shift;
-    hipLaunchKernelGGL(pick_fused(hp->kind, undo, bf16), dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)),
+    hipLaunchKernelGGL(pick_fused(hp->kind, undo, bf16, l->param_bf16 != nullptr), dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)),
                        dim3(64), lds_cap_bytes(info, tune), stream, static_cast<const ChunkDesc *>(plan->chunks()),
                        n_slots, shift, c, slots);
     SWIFT_HIP(hipGetLastError());

@@ -22,10 +22,10 @@
 
 namespace swift {
 
-template <int KIND, bool UNDO>
+template <int KIND, bool UNDO, bool XB>
 struct OptDigestOp {       // step or undo of one element + digest contributions of its new words
   static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
-  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = false;
+  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = XB;
   const OptConsts &c;
   uint32_t elem0;          // index of the chunk's first element inside its tensor
   uint64_t dx = 0, dm = 0, dv = 0;
@@ -39,7 +39,7 @@ struct OptDigestOp {       // step or undo of one element + digest contributions
 };
 
 // One workgroup (one wavefront) per tile; chunk_digest[3c + k] accumulates theta, m, v of chunk c.
-template <int KIND, bool UNDO, bool BF16G, int U, int BLOCK>
+template <int KIND, bool UNDO, bool BF16G, bool XB, int U, int BLOCK>
 __global__ void __launch_bounds__(BLOCK)
 opt_digest_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_shift, const OptConsts c,
                   unsigned long long *__restrict__ chunk_digest) {
@@ -51,8 +51,8 @@ opt_digest_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32
     const ChunkDesc d = fetch_desc(chunks + ci);
     const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
     if (ti * TILE >= d.len) continue;
-    OptDigestOp<KIND, UNDO> op{c, d.elem0};
-    process_tile<OptDigestOp<KIND, UNDO>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
+    OptDigestOp<KIND, UNDO, XB> op{c, d.elem0};
+    process_tile<OptDigestOp<KIND, UNDO, XB>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
     const uint64_t sx = wave_sum_u64(op.dx), sm = wave_sum_u64(op.dm);
     const uint64_t sv = (KIND != kSGDM) ? wave_sum_u64(op.dv) : 0;
     if (threadIdx.x == 0) {

@@ -9,7 +9,7 @@
 // The step is three launches: (1) moments + per-tile partial sums of x^2 and u^2 (reads theta,
 // g, m, v; writes m, v: 24 B per element), (2) a fixed-order reduction of the partials to the two
 // norms of every tensor, (3) the parameter update (reads theta, m, v; writes theta: 16 B per
-// element).  Partial sums are combined in a fixed order (lane tree, then strided sums, then an
+// element, 18 with a bfloat16 copy of theta).  Partial sums are combined in a fixed order (lane tree, then strided sums, then an
 // LDS tree), so the saved norms -- and with them every replica's parameters -- are bit-identical
 // from run to run.  The undo is one launch with AdamW-undo traffic (28 B per element).
 #pragma once
@@ -64,8 +64,9 @@ struct LambMomentsOp {
 };
 
 // Pass 3 of the step: x <- x - (eta q)(r + lambda x), r from the stored new moments.
+template <bool XB>
 struct LambApplyOp {
-  static constexpr bool kLoadG = false, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false, kStoreXB = false;
+  static constexpr bool kLoadG = false, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false, kStoreXB = XB;
   const OptConsts &c;
   double eta_q;
   __device__ __forceinline__ void elem(uint32_t, float &xf, float, float &mf, float &vf) {
@@ -131,7 +132,7 @@ lamb_norms_kernel(const TensorSpan *__restrict__ spans, const double2 *__restric
 }
 
 // Pass 3 of the step: one workgroup per tile.
-template <int U, int BLOCK>
+template <bool XB, int U, int BLOCK>
 __global__ void __launch_bounds__(BLOCK)
 lamb_apply_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_shift, const OptConsts c,
                   const double *__restrict__ norms) {
@@ -141,13 +142,13 @@ lamb_apply_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32
     const ChunkDesc d = fetch_desc(chunks + (w >> tpc_shift));
     const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
     if (ti * TILE >= d.len) continue;
-    LambApplyOp op{c, c.eta * lamb_ratio(norms, d.tensor)};
-    process_tile<LambApplyOp, false, U, BLOCK>(op, d, ti, threadIdx.x);
+    LambApplyOp<XB> op{c, c.eta * lamb_ratio(norms, d.tensor)};
+    process_tile<LambApplyOp<XB>, false, U, BLOCK>(op, d, ti, threadIdx.x);
   } while ((w += gridDim.x) < n_slots);
 }
 
 // Undo: AdamW's undo with eta q in place of eta (q from the saved norms), one workgroup per tile.
-template <bool BF16G, int U, int BLOCK>
+template <bool BF16G, bool XB, int U, int BLOCK>
 __global__ void __launch_bounds__(BLOCK)
 lamb_undo_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_t tpc_shift, const OptConsts c,
                  const double *__restrict__ norms) {
@@ -160,8 +161,8 @@ lamb_undo_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32_
     OptConsts cq = c;
     cq.eta = c.eta * lamb_ratio(norms, d.tensor);
     cq.inv_oml = 1.0 / (1.0 - cq.eta * c.lam);
-    OptOp<kADAMW, true> op{cq};
-    process_tile<OptOp<kADAMW, true>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
+    OptOp<kADAMW, true, XB> op{cq};
+    process_tile<OptOp<kADAMW, true, XB>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
   } while ((w += gridDim.x) < n_slots);
 }
 

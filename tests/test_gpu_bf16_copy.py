@@ -74,16 +74,56 @@ def test_bf16_copy_follows_theta(B, synth, kind, bf16g):
             assert np.array_equal(to_np(xb2[i]), oracle.bf16_round(to_np(b.theta[i])))
 
 
+@pytest.mark.parametrize("bf16g", [False, True], ids=["g_f32", "g_bf16"])
+def test_bf16_copy_in_the_lamb_and_fused_digest_calls(B, synth, bf16g):
+    """Same contract: the copy is the rounding of the theta the call wrote, marked tensors only, and theta, m, v,
+    norms and digests are what the call without the copy gives."""
+    hpd = dict(lr=2e-3, weight_decay=0.01, beta1=0.9, beta2=0.999, eps=1e-6, step=12)
+    w = synth.Workload("t", list(SHAPES), "lamb", hpd, seed=93, grad_bf16=bf16g, zero_frac=0.1, outlier_frac=0.01)
+    a = synth.make_state(w, "cuda", with_v=True)
+    b = a.clone()
+    n = len(SHAPES)
+    sentinel = 0x1234
+    xb = [torch.full((s[0],), 0, dtype=torch.int16, device="cuda").fill_(sentinel).view(torch.bfloat16) for s in SHAPES]
+    tla = B.TensorList(a.theta, a.grad, a.m, a.v, param_bf16=xb)
+    tlb = B.TensorList(b.theta, b.grad, b.m, b.v)
+    mask = [1, 1, 1, 0, 1, 0, 1, 1]
+
+    def same_state_and_copy(m, what):
+        torch.cuda.synchronize()
+        for i in range(n):
+            for x, y in ((a.theta[i], b.theta[i]), (a.m[i], b.m[i]), (a.v[i], b.v[i])):
+                assert torch.equal(x.view(torch.int32), y.view(torch.int32)), f"{what}: the copy changed the arithmetic"
+            if m is None or m[i]:
+                assert np.array_equal(to_np(xb[i]), oracle.bf16_round(to_np(a.theta[i]))), (what, i)
+            else:
+                assert (to_np(xb[i]) == sentinel).all(), f"{what}: copy of an unmarked tensor was written"
+
+    hl = binding_hparams(B, "lamb", hpd, bf16g)
+    na = B.swift_lamb_step(tla, hl, host_mask=mask)
+    nb = B.swift_lamb_step(tlb, hl, host_mask=mask)
+    same_state_and_copy(mask, "lamb step")
+    assert torch.equal(na.view(torch.int64), nb.view(torch.int64))
+    B.swift_lamb_undo(tla, hl, na, host_mask=mask)
+    B.swift_lamb_undo(tlb, hl, nb, host_mask=mask)
+    same_state_and_copy(mask, "lamb undo")
+    hw = binding_hparams(B, "adamw", HP["adamw"], bf16g)
+    for fused in (B.swift_opt_step_digest, B.swift_opt_undo_digest):
+        da = fused(tla, hw, host_mask=mask)
+        db = fused(tlb, hw, host_mask=mask)
+        same_state_and_copy(mask, fused.__name__)
+        assert torch.equal(da, db)
+    da = B.swift_opt_step_digest(tla, hw)
+    db = B.swift_opt_step_digest(tlb, hw)
+    same_state_and_copy(None, "fused step, all tensors")
+    assert torch.equal(da, db)
+
+
 def test_bf16_copy_argument_errors(B, synth):
     w = synth.Workload("t", [(100,)], "adamw", HP["adamw"], seed=1)
     s = synth.make_state(w, "cuda")
     xb = [torch.zeros(100, dtype=torch.bfloat16, device="cuda")]
     tl = B.TensorList(s.theta, s.grad, s.m, s.v, param_bf16=xb)
-    with pytest.raises(B.SwiftError) as e:
-        B.swift_lamb_step(tl, binding_hparams(B, "lamb", HP["adamw"]))
-    assert e.value.code == B.SWIFT_EINVAL and "bfloat16" in e.value.message
-    with pytest.raises(B.SwiftError):
-        B.swift_opt_step_digest(tl, binding_hparams(B, "adamw", HP["adamw"]))
     with pytest.raises(ValueError):
         B.TensorList(s.theta, s.grad, s.m, s.v, param_bf16=[torch.zeros(99, dtype=torch.bfloat16, device="cuda")])
     tl2 = B.TensorList(s.theta, s.grad, s.m, s.v, param_bf16=[s.theta[0].view(torch.bfloat16)[:100]])   # aliases theta
