@@ -38,3 +38,23 @@ def read_digest_vectors():
             ws = [] if lhs.strip() == "-" else [int(s, 16) for s in lhs.split()]
             out.append((ws, int(rhs.strip(), 16)))
     return out
+
+
+def read_grouping_example():
+    """(R, M, T, B, cases) with cases = [(M_max, parallel, group_of, storage, expected_recovery)]."""
+    par, cases = {}, []
+    with open(os.path.join(GOLDEN, "grouping_example.txt")) as fh:
+        for raw in fh:
+            line = raw.split("#", 1)[0].strip()
+            if not line:
+                continue
+            key, rest = line.split(None, 1)
+            if key == "limit":
+                a, b, c = (t.split() for t in rest.split(":"))
+                cases.append((Fraction(a[0]), bool(int(a[1])), [int(t) for t in b], Fraction(c[0]), Fraction(c[1])))
+            elif key in ("R", "M"):
+                par[key] = [Fraction(t) for t in rest.split()]
+            else:
+                par[key] = Fraction(rest)
+    return par["R"], par["M"], par["T"], par["B"], cases
+
