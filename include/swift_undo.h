@@ -238,6 +238,25 @@ int swift_tracker_destroy(swift_tracker *tracker);
  * gives the practical HBM ceiling of this access pattern and calibrates profiler byte counters. */
 int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, void *hip_stream);
 
+/* Machine grouping for selective logging (paper, section "Selective Logging"); host arithmetic only,
+ * no GPU call.  N machines host consecutive pipeline stages; logging keeps the messages between
+ * groups of machines, and a failure rolls back the failed machine's whole group.  Starting from one
+ * group per machine, the adjacent pair with the smallest dR/dM is merged while the logging data of one
+ * checkpoint interval, T * (bytes on the links between groups), exceeds storage_limit, with
+ *   R(G_i,G_{i+1}) = R(G_i) + R(G_{i+1}) + M(G_i,G_{i+1})/B,   dM = M(G_i,G_{i+1}) T,
+ *   dR = R(G_i,G_{i+1})(|G_i|+|G_{i+1}|)/N - R(G_i)|G_i|/N - R(G_{i+1})|G_{i+1}|/N,
+ * and, if parallel_recovery is non-zero, every R(G) in dR divided by floor(N/|G|).  Ties go to the
+ * pair with the lowest index; a link with M = 0 is merged only when no other is left.
+ * compute_time: HOST, n_machines entries, R of each machine (finite, >= 0).  message_bytes: HOST,
+ * n_machines - 1 entries, M between machine i and i+1 (finite, >= 0; may be NULL for one machine).
+ * checkpoint_interval: T > 0 iterations.  bandwidth: B > 0 bytes per time unit of R (infinity allowed).
+ * group_of: HOST, n_machines entries out: group index of each machine, groups numbered from 0 in
+ * pipeline order.  storage_out / recovery_out (nullable): T * bytes on the remaining inter-group links,
+ * and the expected recovery time sum_G R(G)|G|/N of the result.  O(n_machines^2) time. */
+int swift_logging_groups(int64_t n_machines, const double *compute_time, const double *message_bytes,
+                         double checkpoint_interval, double bandwidth, double storage_limit, int parallel_recovery,
+                         int32_t *group_of, double *storage_out, double *recovery_out);
+
 /* Frees every cached table on every device (synchronises those devices first). */
 int swift_shutdown(void);
 

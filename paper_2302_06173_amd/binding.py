@@ -77,7 +77,7 @@ EXPORTS = ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_op
            "swift_tracker_create", "swift_tracker_begin", "swift_tracker_step", "swift_tracker_marks",
            "swift_tracker_undo", "swift_tracker_destroy",
            "swift_state_digest", "swift_digest_count", "swift_mask_from_digests", "swift_stream_copy",
-           "swift_shutdown", "swift_last_error")
+           "swift_logging_groups", "swift_shutdown", "swift_last_error")
 
 
 class SwiftError(RuntimeError):
@@ -347,6 +347,28 @@ def swift_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("stream_copy: sizes differ")
     _check(_lib.swift_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream)))
+
+
+_lib.swift_logging_groups.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_int,
+                                      ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double)]
+_lib.swift_logging_groups.restype = ctypes.c_int
+
+
+def swift_logging_groups(compute_time: Sequence[float], message_bytes: Sequence[float], checkpoint_interval: float,
+                         bandwidth: float, storage_limit: float, parallel_recovery: bool = False):
+    """Machine groups for selective logging: returns (group_of, storage, expected_recovery)."""
+    n = len(compute_time)
+    if len(message_bytes) != max(n - 1, 0):
+        raise ValueError("need one message size per pair of adjacent machines")
+    R = (ctypes.c_double * max(n, 1))(*[float(v) for v in compute_time])
+    M = (ctypes.c_double * max(n - 1, 1))(*[float(v) for v in message_bytes])
+    out = (ctypes.c_int32 * max(n, 1))()
+    storage, recovery = ctypes.c_double(), ctypes.c_double()
+    _check(_lib.swift_logging_groups(n, R, M, float(checkpoint_interval), float(bandwidth), float(storage_limit),
+                                     1 if parallel_recovery else 0, out, ctypes.byref(storage), ctypes.byref(recovery)))
+    return list(out[:n]), storage.value, recovery.value
 
 
 def swift_shutdown() -> None:

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libswift_undo.so")
 SOURCES = [os.path.join(PKG, "csrc", "api.hip")]
 HEADERS = [os.path.join(PKG, "csrc", h) for h in
-           ("opt_kernels.hpp", "digest_kernels.hpp", "lamb_kernels.hpp", "fused_kernels.hpp")] + \
+           ("opt_kernels.hpp", "digest_kernels.hpp", "lamb_kernels.hpp", "fused_kernels.hpp", "logging_groups.hpp")] + \
           [os.path.join(ROOT, "include", "swift_undo.h")]
 EXAMPLE_SRC = os.path.join(PKG, "csrc", "example_undo_roundtrip.c")
 EXAMPLE = os.path.join(PKG, "example_undo_roundtrip.bin")

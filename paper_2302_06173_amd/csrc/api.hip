@@ -22,6 +22,7 @@
 #include "digest_kernels.hpp"
 #include "lamb_kernels.hpp"
 #include "fused_kernels.hpp"
+#include "logging_groups.hpp"
 
 namespace swift {
 namespace {
@@ -1119,6 +1120,34 @@ int swift_tracker_undo(swift_tracker *tr, const swift_tensor_list *list, const s
   if (rc) return rc;
   tracker_recycle(t);
   std::fill(t.marks.begin(), t.marks.end(), 0);   // the state is back at the start of the iteration
+  return SWIFT_OK;
+}
+
+int swift_logging_groups(int64_t n_machines, const double *compute_time, const double *message_bytes,
+                         double checkpoint_interval, double bandwidth, double storage_limit, int parallel_recovery,
+                         int32_t *group_of, double *storage_out, double *recovery_out) {
+  if (n_machines < 1 || n_machines > (int64_t)0x7fffffff) return fail(SWIFT_EINVAL, "n_machines = %lld out of range", (long long)n_machines);
+  if (!compute_time || (n_machines > 1 && !message_bytes) || !group_of)
+    return fail(SWIFT_EINVAL, "compute_time, message_bytes and group_of must not be NULL");
+  if (!(checkpoint_interval > 0) || !std::isfinite(checkpoint_interval))
+    return fail(SWIFT_EINVAL, "checkpoint_interval must be finite and > 0");
+  if (!(bandwidth > 0)) return fail(SWIFT_EINVAL, "bandwidth must be > 0 (infinity allowed)");
+  if (std::isnan(storage_limit)) return fail(SWIFT_EINVAL, "storage_limit is NaN");
+  for (int64_t i = 0; i < n_machines; ++i)
+    if (!(compute_time[i] >= 0) || !std::isfinite(compute_time[i]))
+      return fail(SWIFT_EINVAL, "compute_time[%lld] must be finite and >= 0", (long long)i);
+  for (int64_t i = 0; i + 1 < n_machines; ++i)
+    if (!(message_bytes[i] >= 0) || !std::isfinite(message_bytes[i]))
+      return fail(SWIFT_EINVAL, "message_bytes[%lld] must be finite and >= 0", (long long)i);
+  try {
+    const LoggingGroups r = plan_logging_groups(n_machines, compute_time, message_bytes, checkpoint_interval, bandwidth,
+                                                storage_limit, parallel_recovery != 0);
+    memcpy(group_of, r.group_of.data(), (size_t)n_machines * sizeof(int32_t));
+    if (storage_out) *storage_out = r.storage;
+    if (recovery_out) *recovery_out = r.recovery;
+  } catch (const std::bad_alloc &) {
+    return fail(SWIFT_EHIP, "out of host memory");
+  }
   return SWIFT_OK;
 }
 
