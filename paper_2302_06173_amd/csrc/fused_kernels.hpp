@@ -10,8 +10,8 @@
 // what swift_state_digest returns for the same buffers with one shard per buffer.
 // Measured on MI355X (7B list): the mixer's 32-bit integer multiplies run at half rate, so the
 // digest arithmetic alone sustains about 1.75 T words/s; fused into the update it makes the kernel
-// ALU-bound (step 39.8 ms, undo 36.4 ms) instead of HBM-bound, against 28.6 + 12.7 ms for the
-// two separate passes: a gain of 4-12 %, not the 30 % the saved traffic alone would give.
+// ALU-bound (step 35.3 ms, undo 36.1 ms) instead of HBM-bound, against 28.6 + 12.7 ms for the
+// two separate passes: a gain of 13-14 %, not the 30 % the saved traffic alone would give.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
