@@ -982,13 +982,12 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
   const char *d = static_cast<const char *>(dst_device), *s = static_cast<const char *>(src_device);
   if (d < s + bytes && s < d + bytes) return fail(SWIFT_EINVAL, "stream_copy: ranges overlap");
   const Tuning tune{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK, (int)env_long("SWIFT_WAVES_PER_CU", SWIFT_DEFAULT_WAVES_PER_CU)};
-  const auto kernel = copy_kernel<SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK>;
   const uint64_t n16 = (uint64_t)bytes / 16;
   const uint64_t tile = (uint64_t)SWIFT_DEFAULT_U * SWIFT_DEFAULT_BLOCK;
   const uint64_t tiles = (n16 + tile - 1) / tile;
   const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, 0x7fffffffull);
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(SWIFT_DEFAULT_BLOCK), lds_cap_bytes(info, tune),
-                     static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
+  hipLaunchKernelGGL((copy_kernel<SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK>), dim3(grid), dim3(SWIFT_DEFAULT_BLOCK),
+                     lds_cap_bytes(info, tune), static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
                      static_cast<const u32x4 *>(src_device), n16);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
