@@ -371,10 +371,19 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     if (!host_mask || host_mask[i]) total += n;
   }
   std::sort(iv.begin(), iv.end(), [](const Interval &a, const Interval &b) { return a.lo < b.lo; });
-  for (size_t k = 1; k < iv.size(); ++k)
-    if (iv[k].lo < iv[k - 1].hi && (iv[k].written || iv[k - 1].written))
-      return fail(SWIFT_EINVAL, "buffers overlap: [%p, %p) and [%p, %p)", (void *)iv[k - 1].lo, (void *)iv[k - 1].hi,
-                  (void *)iv[k].lo, (void *)iv[k].hi);
+  // In order of start address, a range overlaps an earlier one iff it starts below the furthest end seen so
+  // far; gradients (read only) may overlap each other, anything that is written may overlap nothing.
+  const Interval *far_any = nullptr, *far_written = nullptr;
+  for (const Interval &cur : iv) {
+    const Interval *hit = nullptr;
+    if (far_written && cur.lo < far_written->hi) hit = far_written;
+    else if (cur.written && far_any && cur.lo < far_any->hi) hit = far_any;
+    if (hit)
+      return fail(SWIFT_EINVAL, "buffers overlap: [%p, %p) and [%p, %p)", (void *)hit->lo, (void *)hit->hi, (void *)cur.lo,
+                  (void *)cur.hi);
+    if (!far_any || cur.hi > far_any->hi) far_any = &cur;
+    if (cur.written && (!far_written || cur.hi > far_written->hi)) far_written = &cur;
+  }
 
   auto plan = std::make_shared<Plan>();
   plan->key = std::move(key);

@@ -365,6 +365,18 @@ def test_bad_device_arguments_are_rejected_on_the_host(B, synth):
     with pytest.raises(B.SwiftError) as e:
         B.swift_opt_undo(tl, hp)
     assert e.value.code == B.SWIFT_EINVAL and "overlap" in e.value.message
+    # gradients may share memory with each other (they are only read), but a long gradient range that also covers
+    # another tensor's parameters is an overlap even when a shorter range starts in between
+    pool = torch.zeros(4000, device="cuda")
+    gshared = [pool[0:1000], pool[0:64]]
+    s2 = s.clone()
+    B.swift_opt_step(B.TensorList(s2.theta, gshared, s2.m, s2.v), hp)          # fine
+    torch.cuda.synchronize()
+    wide = torch.zeros(3000, device="cuda")
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_opt_step(B.TensorList([s.theta[0][:1000], wide[500:564]], [wide[0:1000], wide[10:74]],
+                                      s.m, s.v), hp)
+    assert e.value.code == B.SWIFT_EINVAL and "overlap" in e.value.message
     # not invertible: nothing is enqueued, state untouched
     with pytest.raises(B.SwiftError) as e:
         B.swift_opt_undo(tensor_list(B, s), binding_hparams(B, "adam", dict(HP["adam"], beta1=0.0)))
