@@ -160,6 +160,10 @@ void keep_plan(const std::shared_ptr<Plan> &p) {
 template <typename T>
 void key_add(std::string &k, const T &v) { k.append(reinterpret_cast<const char *>(&v), sizeof v); }
 
+// No buffer of this library's callers can be longer (4 TiB of binary32); the bound keeps byte counts
+// and chunk counts derived from a corrupt numel far away from integer overflow.
+constexpr int64_t kMaxNumel = (int64_t)1 << 40;
+
 // A device range [p, p + bytes) must lie inside one allocation of the current device.
 int check_device_range(const void *p, size_t bytes, int dev, const char *what, int64_t idx) {
   hipPointerAttribute_t attr;
@@ -304,7 +308,8 @@ int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
   if (hasv && !l->v) return fail(SWIFT_EINVAL, "Adam/AdamW need the v array");
   const uintptr_t galign = hp->grad_dtype == SWIFT_BF16 ? 1 : 3;
   for (int64_t i = 0; i < l->n; ++i) {
-    if (l->numel[i] < 0) return fail(SWIFT_EINVAL, "numel[%lld] is negative", (long long)i);
+    if (l->numel[i] < 0 || l->numel[i] > kMaxNumel)
+      return fail(SWIFT_EINVAL, "numel[%lld] = %lld is negative or beyond 2^40", (long long)i, (long long)l->numel[i]);
     if (l->numel[i] == 0) continue;
     if (!l->param[i] || !l->grad[i] || !l->m[i] || (hasv && !l->v[i]))
       return fail(SWIFT_EINVAL, "tensor %lld has a NULL pointer", (long long)i);
@@ -762,7 +767,8 @@ int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, b
     return set_error ? fail(SWIFT_EINVAL, "digest: bad n_buf, numel or shard_elems") : SWIFT_EINVAL;
   int64_t total = 0;
   for (int64_t i = 0; i < n_buf; ++i) {
-    if (numel[i] < 0) return set_error ? fail(SWIFT_EINVAL, "digest: numel[%lld] is negative", (long long)i) : SWIFT_EINVAL;
+    if (numel[i] < 0 || numel[i] > kMaxNumel)
+      return set_error ? fail(SWIFT_EINVAL, "digest: numel[%lld] is negative or beyond 2^40", (long long)i) : SWIFT_EINVAL;
     if (shard_elems == 0) {
       if (numel[i] >= (int64_t)1 << 32)
         return set_error ? fail(SWIFT_EINVAL, "digest: buffer %lld has 2^32 words or more; give shard_elems", (long long)i)
@@ -978,7 +984,8 @@ int swift_mask_from_digests(int64_t n_tensors, int64_t n_groups, const uint64_t 
 }
 
 int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, void *hip_stream) {
-  if (bytes < 0 || (bytes & 15)) return fail(SWIFT_EINVAL, "stream_copy: bytes must be a non-negative multiple of 16");
+  if (bytes < 0 || (bytes & 15) || bytes > 4 * kMaxNumel)
+    return fail(SWIFT_EINVAL, "stream_copy: bytes must be a non-negative multiple of 16 (at most 2^42)");
   if (bytes == 0) return SWIFT_OK;
   if (!dst_device || !src_device) return fail(SWIFT_EINVAL, "stream_copy: NULL pointer");
   if (((uintptr_t)dst_device | (uintptr_t)src_device) & 15) return fail(SWIFT_EINVAL, "stream_copy: pointers must be 16-byte aligned");

@@ -117,6 +117,14 @@ def test_null_and_negative_arguments(B):
     i64 = lambda a: ctypes.cast(a, ctypes.POINTER(ctypes.c_int64))
     lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), c(ptr), i64(neg), None)
     assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    huge = (ctypes.c_int64 * 1)(1 << 62)                   # 4 * numel would wrap around
+    lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), c(ptr), i64(huge), None)
+    assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "2^40" in B.swift_last_error()
+    assert B.swift_digest_count([1 << 20], 1 << 16) == 16
+    with pytest.raises(B.SwiftError):
+        B.swift_digest_count([1 << 62], 1 << 20)
+    assert B._lib.swift_stream_copy(ptr, ptr, 1 << 62, None) == B.SWIFT_EINVAL
     lst = B.SwiftTensorList(n, c(ptr), c(ptr), c(ptr), None, i64(four), None)
     assert B._lib.swift_opt_step(ctypes.byref(lst), ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert "v array" in B.swift_last_error()
