@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
 #include <list>
 #include <memory>
 #include <mutex>
@@ -37,6 +38,18 @@ int fail(int code, const char *fmt, ...) {
   va_end(ap);
   g_last_error = buf;
   return code;
+}
+
+// No C++ exception may cross the C boundary: an entry point's body runs inside guarded().
+template <typename F>
+int guarded(F &&body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    return fail(SWIFT_EHIP, "out of host memory");
+  } catch (const std::exception &e) {
+    return fail(SWIFT_EHIP, "internal error: %s", e.what());
+  }
 }
 
 #define SWIFT_HIP(call)                                                                       \
@@ -888,41 +901,41 @@ using namespace swift;
 extern "C" {
 
 int swift_opt_step(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask, void *hip_stream) {
-  return opt_call(list, hp, host_mask, nullptr, false, false, hip_stream);
+  return guarded([&] { return opt_call(list, hp, host_mask, nullptr, false, false, hip_stream); });
 }
 
 int swift_opt_undo(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask, void *hip_stream) {
-  return opt_call(list, hp, host_mask, nullptr, false, true, hip_stream);
+  return guarded([&] { return opt_call(list, hp, host_mask, nullptr, false, true, hip_stream); });
 }
 
 int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
                          void *hip_stream) {
-  return opt_call(list, hp, nullptr, device_mask, true, false, hip_stream);
+  return guarded([&] { return opt_call(list, hp, nullptr, device_mask, true, false, hip_stream); });
 }
 
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
                          void *hip_stream) {
-  return opt_call(list, hp, nullptr, device_mask, true, true, hip_stream);
+  return guarded([&] { return opt_call(list, hp, nullptr, device_mask, true, true, hip_stream); });
 }
 
 int swift_opt_step_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
                           uint64_t *digests_device, void *hip_stream) {
-  return fused_call(list, hp, host_mask, digests_device, false, hip_stream);
+  return guarded([&] { return fused_call(list, hp, host_mask, digests_device, false, hip_stream); });
 }
 
 int swift_opt_undo_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
                           uint64_t *digests_device, void *hip_stream) {
-  return fused_call(list, hp, host_mask, digests_device, true, hip_stream);
+  return guarded([&] { return fused_call(list, hp, host_mask, digests_device, true, hip_stream); });
 }
 
 int swift_lamb_step(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
                     double *norms_device, void *hip_stream) {
-  return lamb_call(list, hp, host_mask, norms_device, false, hip_stream);
+  return guarded([&] { return lamb_call(list, hp, host_mask, norms_device, false, hip_stream); });
 }
 
 int swift_lamb_undo(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
                     const double *norms_device, void *hip_stream) {
-  return lamb_call(list, hp, host_mask, const_cast<double *>(norms_device), true, hip_stream);
+  return guarded([&] { return lamb_call(list, hp, host_mask, const_cast<double *>(norms_device), true, hip_stream); });
 }
 
 int64_t swift_digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems) {
@@ -931,82 +944,88 @@ int64_t swift_digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_el
 
 int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *numel, int64_t shard_elems,
                        uint64_t *out_device, void *hip_stream) {
-  const int64_t n_out = digest_count(n_buf, numel, shard_elems, true);
-  if (n_out < 0) return (int)n_out;
-  if (n_buf > 0 && !buf) return fail(SWIFT_EINVAL, "digest: buf array is NULL");
-  if (n_out == 0) return SWIFT_OK;
-  if (!out_device) return fail(SWIFT_EINVAL, "digest: out_device is NULL");
-  if ((uintptr_t)out_device & 7) return fail(SWIFT_EINVAL, "digest: out_device is not 8-byte aligned");
-  int dev = -1, rc;
-  SWIFT_HIP(hipGetDevice(&dev));
-  DeviceInfo info;
-  if ((rc = device_info(dev, &info))) return rc;
-  if ((rc = check_device_range(out_device, (size_t)n_out * 8, dev, "out_device", 0))) return rc;
-  const long du = env_long("SWIFT_DIGEST_U", SWIFT_DIGEST_U);   // tuning knob for sweeps
-  const auto kernel = du == 1 ? digest_kernel<1> : du == 2 ? digest_kernel<2> : digest_kernel<4>;
-  std::shared_ptr<Plan> plan;
-  if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, info.cus, &plan))) return rc;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  // The output is cleared by a kernel (not a memset node) so that the call can be captured in a graph.
-  const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(fill_grid), dim3(kThreads), 0, stream, out_device, (uint64_t)n_out,
-                     (uint64_t)0);
-  SWIFT_HIP(hipGetLastError());
-  if (plan->n_chunks == 0) return SWIFT_OK;
-  const uint32_t grid = plan->n_chunks;                        // one workgroup per chunk
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
-                     static_cast<const ChunkRef *>(plan->chunks()), plan->n_chunks, plan->chunk_elems,
-                     (uint64_t)shard_elems,
-                     reinterpret_cast<unsigned long long *>(out_device));
-  SWIFT_HIP(hipGetLastError());
-  return SWIFT_OK;
+  return guarded([&]() -> int {
+    const int64_t n_out = digest_count(n_buf, numel, shard_elems, true);
+    if (n_out < 0) return (int)n_out;
+    if (n_buf > 0 && !buf) return fail(SWIFT_EINVAL, "digest: buf array is NULL");
+    if (n_out == 0) return SWIFT_OK;
+    if (!out_device) return fail(SWIFT_EINVAL, "digest: out_device is NULL");
+    if ((uintptr_t)out_device & 7) return fail(SWIFT_EINVAL, "digest: out_device is not 8-byte aligned");
+    int dev = -1, rc;
+    SWIFT_HIP(hipGetDevice(&dev));
+    DeviceInfo info;
+    if ((rc = device_info(dev, &info))) return rc;
+    if ((rc = check_device_range(out_device, (size_t)n_out * 8, dev, "out_device", 0))) return rc;
+    const long du = env_long("SWIFT_DIGEST_U", SWIFT_DIGEST_U);   // tuning knob for sweeps
+    const auto kernel = du == 1 ? digest_kernel<1> : du == 2 ? digest_kernel<2> : digest_kernel<4>;
+    std::shared_ptr<Plan> plan;
+    if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, info.cus, &plan))) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // The output is cleared by a kernel (not a memset node) so that the call can be captured in a graph.
+    const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(fill_grid), dim3(kThreads), 0, stream, out_device, (uint64_t)n_out,
+                       (uint64_t)0);
+    SWIFT_HIP(hipGetLastError());
+    if (plan->n_chunks == 0) return SWIFT_OK;
+    const uint32_t grid = plan->n_chunks;                        // one workgroup per chunk
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
+                       static_cast<const ChunkRef *>(plan->chunks()), plan->n_chunks, plan->chunk_elems,
+                       (uint64_t)shard_elems,
+                       reinterpret_cast<unsigned long long *>(out_device));
+    SWIFT_HIP(hipGetLastError());
+    return SWIFT_OK;
+  });
 }
 
 int swift_mask_from_digests(int64_t n_tensors, int64_t n_groups, const uint64_t *before_device,
                             const uint64_t *after_device, uint8_t *mask_device, void *hip_stream) {
-  if (n_tensors < 0 || n_tensors > (int64_t)0x7fffffff || n_groups < 1 || n_groups > 64)
-    return fail(SWIFT_EINVAL, "mask_from_digests: n_tensors or n_groups out of range");
-  if (n_tensors == 0) return SWIFT_OK;
-  if (!before_device || !after_device || !mask_device) return fail(SWIFT_EINVAL, "mask_from_digests: NULL pointer");
-  if (((uintptr_t)before_device | (uintptr_t)after_device) & 7)
-    return fail(SWIFT_EINVAL, "mask_from_digests: digest arrays are not 8-byte aligned");
-  int dev = -1, rc;
-  SWIFT_HIP(hipGetDevice(&dev));
-  const size_t dbytes = (size_t)n_tensors * (size_t)n_groups * 8;
-  if ((rc = check_device_range(before_device, dbytes, dev, "before_device", 0))) return rc;
-  if ((rc = check_device_range(after_device, dbytes, dev, "after_device", 0))) return rc;
-  if ((rc = check_device_range(mask_device, (size_t)n_tensors, dev, "mask_device", 0))) return rc;
-  const uint32_t grid = (uint32_t)std::min<int64_t>((n_tensors + kThreads - 1) / kThreads, 1024);
-  hipLaunchKernelGGL(mask_from_digests_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
-                     (uint32_t)n_tensors, (uint32_t)n_groups, before_device, after_device, mask_device);
-  SWIFT_HIP(hipGetLastError());
-  return SWIFT_OK;
+  return guarded([&]() -> int {
+    if (n_tensors < 0 || n_tensors > (int64_t)0x7fffffff || n_groups < 1 || n_groups > 64)
+      return fail(SWIFT_EINVAL, "mask_from_digests: n_tensors or n_groups out of range");
+    if (n_tensors == 0) return SWIFT_OK;
+    if (!before_device || !after_device || !mask_device) return fail(SWIFT_EINVAL, "mask_from_digests: NULL pointer");
+    if (((uintptr_t)before_device | (uintptr_t)after_device) & 7)
+      return fail(SWIFT_EINVAL, "mask_from_digests: digest arrays are not 8-byte aligned");
+    int dev = -1, rc;
+    SWIFT_HIP(hipGetDevice(&dev));
+    const size_t dbytes = (size_t)n_tensors * (size_t)n_groups * 8;
+    if ((rc = check_device_range(before_device, dbytes, dev, "before_device", 0))) return rc;
+    if ((rc = check_device_range(after_device, dbytes, dev, "after_device", 0))) return rc;
+    if ((rc = check_device_range(mask_device, (size_t)n_tensors, dev, "mask_device", 0))) return rc;
+    const uint32_t grid = (uint32_t)std::min<int64_t>((n_tensors + kThreads - 1) / kThreads, 1024);
+    hipLaunchKernelGGL(mask_from_digests_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       (uint32_t)n_tensors, (uint32_t)n_groups, before_device, after_device, mask_device);
+    SWIFT_HIP(hipGetLastError());
+    return SWIFT_OK;
+  });
 }
 
 int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, void *hip_stream) {
-  if (bytes < 0 || (bytes & 15) || bytes > 4 * kMaxNumel)
-    return fail(SWIFT_EINVAL, "stream_copy: bytes must be a non-negative multiple of 16 (at most 2^42)");
-  if (bytes == 0) return SWIFT_OK;
-  if (!dst_device || !src_device) return fail(SWIFT_EINVAL, "stream_copy: NULL pointer");
-  if (((uintptr_t)dst_device | (uintptr_t)src_device) & 15) return fail(SWIFT_EINVAL, "stream_copy: pointers must be 16-byte aligned");
-  int dev = -1, rc;
-  SWIFT_HIP(hipGetDevice(&dev));
-  DeviceInfo info;
-  if ((rc = device_info(dev, &info))) return rc;
-  if ((rc = check_device_range(dst_device, (size_t)bytes, dev, "dst_device", 0))) return rc;
-  if ((rc = check_device_range(src_device, (size_t)bytes, dev, "src_device", 0))) return rc;
-  const char *d = static_cast<const char *>(dst_device), *s = static_cast<const char *>(src_device);
-  if (d < s + bytes && s < d + bytes) return fail(SWIFT_EINVAL, "stream_copy: ranges overlap");
-  const Tuning tune{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK, (int)env_long("SWIFT_WAVES_PER_CU", SWIFT_DEFAULT_WAVES_PER_CU)};
-  const uint64_t n16 = (uint64_t)bytes / 16;
-  const uint64_t tile = (uint64_t)SWIFT_DEFAULT_U * SWIFT_DEFAULT_BLOCK;
-  const uint64_t tiles = (n16 + tile - 1) / tile;
-  const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, 0x7fffffffull);
-  hipLaunchKernelGGL((copy_kernel<SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK>), dim3(grid), dim3(SWIFT_DEFAULT_BLOCK),
-                     lds_cap_bytes(info, tune), static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
-                     static_cast<const u32x4 *>(src_device), n16);
-  SWIFT_HIP(hipGetLastError());
-  return SWIFT_OK;
+  return guarded([&]() -> int {
+    if (bytes < 0 || (bytes & 15) || bytes > 4 * kMaxNumel)
+      return fail(SWIFT_EINVAL, "stream_copy: bytes must be a non-negative multiple of 16 (at most 2^42)");
+    if (bytes == 0) return SWIFT_OK;
+    if (!dst_device || !src_device) return fail(SWIFT_EINVAL, "stream_copy: NULL pointer");
+    if (((uintptr_t)dst_device | (uintptr_t)src_device) & 15) return fail(SWIFT_EINVAL, "stream_copy: pointers must be 16-byte aligned");
+    int dev = -1, rc;
+    SWIFT_HIP(hipGetDevice(&dev));
+    DeviceInfo info;
+    if ((rc = device_info(dev, &info))) return rc;
+    if ((rc = check_device_range(dst_device, (size_t)bytes, dev, "dst_device", 0))) return rc;
+    if ((rc = check_device_range(src_device, (size_t)bytes, dev, "src_device", 0))) return rc;
+    const char *d = static_cast<const char *>(dst_device), *s = static_cast<const char *>(src_device);
+    if (d < s + bytes && s < d + bytes) return fail(SWIFT_EINVAL, "stream_copy: ranges overlap");
+    const Tuning tune{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK, (int)env_long("SWIFT_WAVES_PER_CU", SWIFT_DEFAULT_WAVES_PER_CU)};
+    const uint64_t n16 = (uint64_t)bytes / 16;
+    const uint64_t tile = (uint64_t)SWIFT_DEFAULT_U * SWIFT_DEFAULT_BLOCK;
+    const uint64_t tiles = (n16 + tile - 1) / tile;
+    const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, 0x7fffffffull);
+    hipLaunchKernelGGL((copy_kernel<SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK>), dim3(grid), dim3(SWIFT_DEFAULT_BLOCK),
+                       lds_cap_bytes(info, tune), static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
+                       static_cast<const u32x4 *>(src_device), n16);
+    SWIFT_HIP(hipGetLastError());
+    return SWIFT_OK;
+  });
 }
 
 struct swift_tracker {
@@ -1014,15 +1033,17 @@ struct swift_tracker {
 };
 
 int swift_tracker_create(int64_t n_tensors, swift_tracker **out) {
-  if (!out) return fail(SWIFT_EINVAL, "tracker: out is NULL");
-  *out = nullptr;
-  if (n_tensors < 0 || n_tensors > (int64_t)0x7fffffff) return fail(SWIFT_EINVAL, "tracker: tensor count out of range");
-  swift_tracker *tr = new (std::nothrow) swift_tracker();
-  if (!tr) return fail(SWIFT_EHIP, "tracker: out of host memory");
-  tr->t.n_tensors = n_tensors;
-  tr->t.marks.assign((size_t)n_tensors, 0);
-  *out = tr;
-  return SWIFT_OK;
+  return guarded([&]() -> int {
+    if (!out) return fail(SWIFT_EINVAL, "tracker: out is NULL");
+    *out = nullptr;
+    if (n_tensors < 0 || n_tensors > (int64_t)0x7fffffff) return fail(SWIFT_EINVAL, "tracker: tensor count out of range");
+    swift_tracker *tr = new (std::nothrow) swift_tracker();
+    if (!tr) return fail(SWIFT_EHIP, "tracker: out of host memory");
+    tr->t.n_tensors = n_tensors;
+    tr->t.marks.assign((size_t)n_tensors, 0);
+    *out = tr;
+    return SWIFT_OK;
+  });
 }
 
 int swift_tracker_destroy(swift_tracker *tr) {
@@ -1055,58 +1076,60 @@ int swift_tracker_begin(swift_tracker *tr, int64_t step) {
 
 int swift_tracker_step(swift_tracker *tr, const swift_tensor_list *group, const int64_t *tensor_ids,
                        const swift_hparams *hp, void *grad_ready_event, void *hip_stream) {
-  if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
-  if (!group || !hp) return fail(SWIFT_EINVAL, "tracker: group or hparams is NULL");
-  if (group->n > 0 && !tensor_ids) return fail(SWIFT_EINVAL, "tracker: tensor_ids is NULL");
-  Tracker &t = tr->t;
-  std::lock_guard<std::mutex> lock(t.mu);
-  if (t.step == 0) return fail(SWIFT_EINVAL, "tracker: swift_tracker_begin has not been called");
-  if (hp->step != t.step)
-    return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
-                (long long)t.step);
-  for (int64_t k = 0; k < group->n; ++k) {
-    const int64_t id = tensor_ids[k];
-    if (id < 0 || id >= t.n_tensors) return fail(SWIFT_EINVAL, "tracker: tensor id %lld out of range", (long long)id);
-    if (t.marks[(size_t)id]) return fail(SWIFT_EINVAL, "tracker: tensor %lld was already updated in this iteration", (long long)id);
-    for (int64_t j = 0; j < k; ++j)
-      if (tensor_ids[j] == id) return fail(SWIFT_EINVAL, "tracker: tensor id %lld appears twice", (long long)id);
-  }
-  int dev = -1;
-  SWIFT_HIP(hipGetDevice(&dev));
-  if (t.device < 0) t.device = dev;
-  if (dev != t.device) return fail(SWIFT_EINVAL, "tracker: created for device %d, current device is %d", t.device, dev);
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipEvent_t done;
-  if (!t.pool.empty()) {
-    done = t.pool.back();
-    t.pool.pop_back();
-  } else {
-    SWIFT_HIP(hipEventCreateWithFlags(&done, hipEventDisableTiming));
-  }
-  // the update waits (on the device) for the gradient to be final, as the paper's loop waits for the
-  // all-reduce of that tensor before launching its update kernels
-  if (grad_ready_event) {
-    hipError_t e = hipStreamWaitEvent(stream, static_cast<hipEvent_t>(grad_ready_event), 0);
-    if (e != hipSuccess) {
-      t.pool.push_back(done);
-      return fail(SWIFT_EHIP, "hipStreamWaitEvent failed: %s", hipGetErrorName(e));
+  return guarded([&]() -> int {
+    if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
+    if (!group || !hp) return fail(SWIFT_EINVAL, "tracker: group or hparams is NULL");
+    if (group->n > 0 && !tensor_ids) return fail(SWIFT_EINVAL, "tracker: tensor_ids is NULL");
+    Tracker &t = tr->t;
+    std::lock_guard<std::mutex> lock(t.mu);
+    if (t.step == 0) return fail(SWIFT_EINVAL, "tracker: swift_tracker_begin has not been called");
+    if (hp->step != t.step)
+      return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
+                  (long long)t.step);
+    for (int64_t k = 0; k < group->n; ++k) {
+      const int64_t id = tensor_ids[k];
+      if (id < 0 || id >= t.n_tensors) return fail(SWIFT_EINVAL, "tracker: tensor id %lld out of range", (long long)id);
+      if (t.marks[(size_t)id]) return fail(SWIFT_EINVAL, "tracker: tensor %lld was already updated in this iteration", (long long)id);
+      for (int64_t j = 0; j < k; ++j)
+        if (tensor_ids[j] == id) return fail(SWIFT_EINVAL, "tracker: tensor id %lld appears twice", (long long)id);
     }
-  }
-  const int rc = swift_opt_step(group, hp, nullptr, hip_stream);
-  if (rc != SWIFT_OK) {
-    t.pool.push_back(done);
-    return rc;                         // nothing was launched, nothing is marked
-  }
-  hipError_t e = hipEventRecord(done, stream);
-  if (e != hipSuccess) {
-    // the kernels are in flight but cannot be tracked by an event: wait for them here, then mark
-    (void)hipStreamSynchronize(stream);
-    t.pool.push_back(done);
-  } else {
-    t.pending.push_back(done);
-  }
-  for (int64_t k = 0; k < group->n; ++k) t.marks[(size_t)tensor_ids[k]] = 1;
-  return SWIFT_OK;
+    int dev = -1;
+    SWIFT_HIP(hipGetDevice(&dev));
+    if (t.device < 0) t.device = dev;
+    if (dev != t.device) return fail(SWIFT_EINVAL, "tracker: created for device %d, current device is %d", t.device, dev);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t done;
+    if (!t.pool.empty()) {
+      done = t.pool.back();
+      t.pool.pop_back();
+    } else {
+      SWIFT_HIP(hipEventCreateWithFlags(&done, hipEventDisableTiming));
+    }
+    // the update waits (on the device) for the gradient to be final, as the paper's loop waits for the
+    // all-reduce of that tensor before launching its update kernels
+    if (grad_ready_event) {
+      hipError_t e = hipStreamWaitEvent(stream, static_cast<hipEvent_t>(grad_ready_event), 0);
+      if (e != hipSuccess) {
+        t.pool.push_back(done);
+        return fail(SWIFT_EHIP, "hipStreamWaitEvent failed: %s", hipGetErrorName(e));
+      }
+    }
+    const int rc = swift_opt_step(group, hp, nullptr, hip_stream);
+    if (rc != SWIFT_OK) {
+      t.pool.push_back(done);
+      return rc;                         // nothing was launched, nothing is marked
+    }
+    hipError_t e = hipEventRecord(done, stream);
+    if (e != hipSuccess) {
+      // the kernels are in flight but cannot be tracked by an event: wait for them here, then mark
+      (void)hipStreamSynchronize(stream);
+      t.pool.push_back(done);
+    } else {
+      t.pending.push_back(done);
+    }
+    for (int64_t k = 0; k < group->n; ++k) t.marks[(size_t)tensor_ids[k]] = 1;
+    return SWIFT_OK;
+  });
 }
 
 int swift_tracker_marks(swift_tracker *tr, uint8_t *host_mask_out) {
@@ -1121,21 +1144,23 @@ int swift_tracker_marks(swift_tracker *tr, uint8_t *host_mask_out) {
 }
 
 int swift_tracker_undo(swift_tracker *tr, const swift_tensor_list *list, const swift_hparams *hp, void *hip_stream) {
-  if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
-  if (!list || !hp) return fail(SWIFT_EINVAL, "tracker: list or hparams is NULL");
-  Tracker &t = tr->t;
-  std::lock_guard<std::mutex> lock(t.mu);
-  if (list->n != t.n_tensors) return fail(SWIFT_EINVAL, "tracker: the list has %lld tensors, the tracker %lld", (long long)list->n, (long long)t.n_tensors);
-  if (t.step == 0 || hp->step != t.step)
-    return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
-                (long long)t.step);
-  int rc = tracker_wait(t);
-  if (rc) return rc;
-  rc = swift_opt_undo(list, hp, t.marks.data(), hip_stream);
-  if (rc) return rc;
-  tracker_recycle(t);
-  std::fill(t.marks.begin(), t.marks.end(), 0);   // the state is back at the start of the iteration
-  return SWIFT_OK;
+  return guarded([&]() -> int {
+    if (!tr) return fail(SWIFT_EINVAL, "tracker is NULL");
+    if (!list || !hp) return fail(SWIFT_EINVAL, "tracker: list or hparams is NULL");
+    Tracker &t = tr->t;
+    std::lock_guard<std::mutex> lock(t.mu);
+    if (list->n != t.n_tensors) return fail(SWIFT_EINVAL, "tracker: the list has %lld tensors, the tracker %lld", (long long)list->n, (long long)t.n_tensors);
+    if (t.step == 0 || hp->step != t.step)
+      return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
+                  (long long)t.step);
+    int rc = tracker_wait(t);
+    if (rc) return rc;
+    rc = swift_opt_undo(list, hp, t.marks.data(), hip_stream);
+    if (rc) return rc;
+    tracker_recycle(t);
+    std::fill(t.marks.begin(), t.marks.end(), 0);   // the state is back at the start of the iteration
+    return SWIFT_OK;
+  });
 }
 
 int swift_logging_groups(int64_t n_machines, const double *compute_time, const double *message_bytes,
@@ -1154,16 +1179,14 @@ int swift_logging_groups(int64_t n_machines, const double *compute_time, const d
   for (int64_t i = 0; i + 1 < n_machines; ++i)
     if (!(message_bytes[i] >= 0) || !std::isfinite(message_bytes[i]))
       return fail(SWIFT_EINVAL, "message_bytes[%lld] must be finite and >= 0", (long long)i);
-  try {
+  return guarded([&]() -> int {
     const LoggingGroups r = plan_logging_groups(n_machines, compute_time, message_bytes, checkpoint_interval, bandwidth,
                                                 storage_limit, parallel_recovery != 0);
     memcpy(group_of, r.group_of.data(), (size_t)n_machines * sizeof(int32_t));
     if (storage_out) *storage_out = r.storage;
     if (recovery_out) *recovery_out = r.recovery;
-  } catch (const std::bad_alloc &) {
-    return fail(SWIFT_EHIP, "out of host memory");
-  }
-  return SWIFT_OK;
+    return SWIFT_OK;
+  });
 }
 
 int swift_shutdown(void) {
