@@ -43,7 +43,8 @@ typedef enum {
                                 allocation is shorter than numel elements, misaligned pointer */
   SWIFT_ENOTINVERTIBLE = -2, /* undo only: the inverse divides by zero (beta1 = 0, beta2 = 0, or
                                 eta*lambda = 1 for AdamW) */
-  SWIFT_EHIP = -3            /* a HIP runtime call failed; the message carries its error name */
+  SWIFT_EHIP = -3            /* a HIP runtime call failed (the message carries its error name), or the
+                                library could not get host memory; no C++ exception leaves the library */
 } swift_status;
 
 typedef enum {
