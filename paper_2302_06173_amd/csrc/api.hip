@@ -1086,13 +1086,32 @@ int swift_tracker_step(swift_tracker *tr, const swift_tensor_list *group, const 
     if (hp->step != t.step)
       return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
                   (long long)t.step);
-    for (int64_t k = 0; k < group->n; ++k) {
-      const int64_t id = tensor_ids[k];
-      if (id < 0 || id >= t.n_tensors) return fail(SWIFT_EINVAL, "tracker: tensor id %lld out of range", (long long)id);
-      if (t.marks[(size_t)id]) return fail(SWIFT_EINVAL, "tracker: tensor %lld was already updated in this iteration", (long long)id);
-      for (int64_t j = 0; j < k; ++j)
-        if (tensor_ids[j] == id) return fail(SWIFT_EINVAL, "tracker: tensor id %lld appears twice", (long long)id);
+    // validate the ids in one pass: 2 = "named by this call" while the call is being checked
+    int bad = SWIFT_OK;
+    int64_t checked = 0;
+    for (; checked < group->n && bad == SWIFT_OK; ++checked) {
+      const int64_t id = tensor_ids[checked];
+      if (id < 0 || id >= t.n_tensors) bad = fail(SWIFT_EINVAL, "tracker: tensor id %lld out of range", (long long)id);
+      else if (t.marks[(size_t)id] == 1) bad = fail(SWIFT_EINVAL, "tracker: tensor %lld was already updated in this iteration", (long long)id);
+      else if (t.marks[(size_t)id] == 2) bad = fail(SWIFT_EINVAL, "tracker: tensor id %lld appears twice", (long long)id);
+      else t.marks[(size_t)id] = 2;
     }
+    auto unmark = [&](int64_t upto) {
+      for (int64_t k = 0; k < upto; ++k) {
+        const int64_t id = tensor_ids[k];
+        if (id >= 0 && id < t.n_tensors && t.marks[(size_t)id] == 2) t.marks[(size_t)id] = 0;
+      }
+    };
+    if (bad != SWIFT_OK) {
+      unmark(checked);
+      return bad;
+    }
+    struct Rollback {                    // any early return below leaves no tensor half-marked
+      decltype(unmark) &undo;
+      int64_t n;
+      bool armed = true;
+      ~Rollback() { if (armed) undo(n); }
+    } rollback{unmark, group->n};
     int dev = -1;
     SWIFT_HIP(hipGetDevice(&dev));
     if (t.device < 0) t.device = dev;
@@ -1127,6 +1146,7 @@ int swift_tracker_step(swift_tracker *tr, const swift_tensor_list *group, const 
     } else {
       t.pending.push_back(done);
     }
+    rollback.armed = false;
     for (int64_t k = 0; k < group->n; ++k) t.marks[(size_t)tensor_ids[k]] = 1;
     return SWIFT_OK;
   });

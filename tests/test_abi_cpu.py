@@ -193,6 +193,13 @@ def test_tracker_host_logic_without_a_gpu(B):
     assert B._lib.swift_tracker_step(h, ctypes.byref(one), bad, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     assert "out of range" in B.swift_last_error()
     assert B._lib.swift_tracker_step(h, ctypes.byref(one), None, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    # an id named twice in one call is refused before anything is launched, and leaves no mark behind
+    two = B.SwiftTensorList(2, None, None, None, None, None, None)
+    dup = (ctypes.c_int64 * 2)(1, 1)
+    assert B._lib.swift_tracker_step(h, ctypes.byref(two), dup, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
+    assert "twice" in B.swift_last_error()
+    mixed = (ctypes.c_int64 * 2)(2, 9)
+    assert B._lib.swift_tracker_step(h, ctypes.byref(two), mixed, ctypes.byref(hp), None, None) == B.SWIFT_EINVAL
     marks = (ctypes.c_uint8 * 3)(9, 9, 9)
     assert B._lib.swift_tracker_marks(h, ctypes.cast(marks, ctypes.c_void_p)) == B.SWIFT_OK    # nothing pending
     assert list(marks) == [0, 0, 0]
