@@ -83,29 +83,48 @@ def cpu_baseline(w, state, hp_dict, sample_elems: int):
     oh = oracle.Hyper("adamw", eta=hp_dict["lr"], lam=hp_dict["weight_decay"], beta1=hp_dict["beta1"],
                       beta2=hp_dict["beta2"], eps=hp_dict["eps"], t=hp_dict["step"])
     bounds = [n * k // cores for k in range(cores + 1)]
+    stepped = [None] * cores
 
-    def work(k):
+    def do_step(k):
         lo, hi = bounds[k], bounds[k + 1]
-        sx, sm, sv = oracle.opt_step(oh, x[lo:hi], g[lo:hi], m[lo:hi], v[lo:hi])
+        stepped[k] = oracle.opt_step(oh, x[lo:hi], g[lo:hi], m[lo:hi], v[lo:hi])
+
+    def do_undo(k):
+        lo, hi = bounds[k], bounds[k + 1]
+        sx, sm, sv = stepped[k]
         oracle.opt_undo(oh, sx, g[lo:hi], sm, sv)
+
+    def do_digest(k):
+        lo, hi = bounds[k], bounds[k + 1]
         for a in (x32, m32, v32):
             oracle.digest(a[lo:hi])
 
-    best = None
+    best = {}
     with cf.ThreadPoolExecutor(cores) as pool:
         for _ in range(3):                       # first round also warms the allocator's pages
-            t0 = time.perf_counter()
-            list(pool.map(work, range(cores)))
-            dt = time.perf_counter() - t0
-            best = dt if best is None else min(best, dt)
+            for name, fn in (("adamw_step", do_step), ("adamw_undo", do_undo), ("digest", do_digest)):
+                t0 = time.perf_counter()
+                list(pool.map(fn, range(cores)))
+                dt = time.perf_counter() - t0
+                best[name] = dt if name not in best else min(best[name], dt)
     n1 = n // cores
     t0 = time.perf_counter()
     sx, sm, sv = oracle.opt_step(oh, x[:n1], g[:n1], m[:n1], v[:n1])
     oracle.opt_undo(oh, sx, g[:n1], sm, sv)
     t1 = time.perf_counter() - t0
-    return {"value": 2 * n / best, "unit": "params/s", "cores": cores, "kind": "oracle",
-            "sample": f"AdamW step+undo and 3 digests on the first {n} elements of the {w.name} list, "
-                      f"static split over {cores} threads, best of 3",
+    g_bytes = 2 if state.grad[0].dtype == torch.bfloat16 else 4
+    per_kernel = {
+        "adamw_step": {"gparams_per_s": round(n / best["adamw_step"] / 1e9, 3),
+                       "gb_per_s": round((24 + g_bytes) * n / best["adamw_step"] / 1e9, 1)},
+        "adamw_undo": {"gparams_per_s": round(n / best["adamw_undo"] / 1e9, 3),
+                       "gb_per_s": round((24 + g_bytes) * n / best["adamw_undo"] / 1e9, 1)},
+        "digest_theta_m_v": {"gb_per_s": round(12 * n / best["digest"] / 1e9, 1)},
+    }
+    whole = best["adamw_step"] + best["adamw_undo"] + best["digest"]
+    return {"value": 2 * n / whole, "unit": "params/s", "cores": cores, "kind": "oracle",
+            "sample": f"AdamW step, undo and 3 digests on the first {n} elements of the {w.name} list, each timed on its own, "
+                      f"static split over {cores} threads, best of 3; value = 2 x elements / (step + undo + digest time)",
+            "per_kernel": per_kernel,
             "single_thread_value": 2 * n1 / t1}
 
 
@@ -271,6 +290,21 @@ def main() -> int:
         B.swift_opt_undo_dmask(tl_adam, hp_w, dmask)
     extra("adamw_step_undo_device_mask", masked_pair, 24 + g_bytes, 2 * n_masked)
 
+    # The chip's own 1-read/1-write ceiling with the same launch style (a plain copy of 4 GiB), measured here so
+    # that the roofline fraction can also be read against what this GPU delivers, not only against the data sheet.
+    ceil_src = torch.empty(1 << 32, dtype=torch.uint8, device="cuda").fill_(0x3c)
+    ceil_dst = torch.empty_like(ceil_src)
+    B.swift_stream_copy(ceil_dst, ceil_src)
+    cev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+    cev[0].record()
+    for k in range(5):
+        B.swift_stream_copy(ceil_dst, ceil_src)
+        cev[k + 1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * ceil_src.numel() / min(cev[k].elapsed_time(cev[k + 1]) for k in range(5)) / 1e6
+    del ceil_src, ceil_dst
+    log(f"[bench] copy ceiling (4 GiB, best of 5): {copy_gbs:.0f} GB/s")
+
     seg_all = {s: sorted(ev[k].elapsed_time(ev[k + 1]) for ev in all_events) for k, s in enumerate(segs)}
     seg_ms = {s: sum(v) / max(len(v), 1) for s, v in seg_all.items()}
     params_per_pass = sum(seg_params.values())
@@ -304,6 +338,7 @@ def main() -> int:
                                                  "(selective undo of the marked tensors, full list)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
+                     "measured_copy_gb_per_s": copy_gbs, "frac_of_measured_copy": achieved / copy_gbs,
                      "gparams_per_s": dom_params / dom_ms / 1e6},
         "kernels": kernels,
         "extras": extras,

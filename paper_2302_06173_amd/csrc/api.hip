@@ -1015,14 +1015,23 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
     if ((rc = check_device_range(src_device, (size_t)bytes, dev, "src_device", 0))) return rc;
     const char *d = static_cast<const char *>(dst_device), *s = static_cast<const char *>(src_device);
     if (d < s + bytes && s < d + bytes) return fail(SWIFT_EINVAL, "stream_copy: ranges overlap");
-    const Tuning tune{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK, (int)env_long("SWIFT_WAVES_PER_CU", SWIFT_DEFAULT_WAVES_PER_CU)};
+    // A copy moves only 2 x 16 bytes per lane, so unlike the update kernels it wants every wavefront slot of
+    // a CU filled: one vector per lane and no residency cap measured best (6.7 TB/s; 4.3 with the update
+    // kernels' cap of 11).  Knobs for sweeps.
+    const int u = clamp_u(env_long("SWIFT_COPY_U", SWIFT_COPY_U));
+    const Tuning tune{u, SWIFT_DEFAULT_BLOCK, (int)env_long("SWIFT_COPY_WAVES_PER_CU", SWIFT_COPY_WAVES_PER_CU)};
     const uint64_t n16 = (uint64_t)bytes / 16;
-    const uint64_t tile = (uint64_t)SWIFT_DEFAULT_U * SWIFT_DEFAULT_BLOCK;
+    const uint64_t tile = (uint64_t)u * SWIFT_DEFAULT_BLOCK;
     const uint64_t tiles = (n16 + tile - 1) / tile;
     const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, 0x7fffffffull);
-    hipLaunchKernelGGL((copy_kernel<SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK>), dim3(grid), dim3(SWIFT_DEFAULT_BLOCK),
-                       lds_cap_bytes(info, tune), static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
-                       static_cast<const u32x4 *>(src_device), n16);
+    const auto launch = [&](auto kernel) {
+      hipLaunchKernelGGL(kernel, dim3(grid), dim3(SWIFT_DEFAULT_BLOCK), lds_cap_bytes(info, tune),
+                         static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
+                         static_cast<const u32x4 *>(src_device), n16);
+    };
+    if (u == 1) launch(copy_kernel<1, SWIFT_DEFAULT_BLOCK>);
+    else if (u == 2) launch(copy_kernel<2, SWIFT_DEFAULT_BLOCK>);
+    else launch(copy_kernel<4, SWIFT_DEFAULT_BLOCK>);
     SWIFT_HIP(hipGetLastError());
     return SWIFT_OK;
   });

@@ -96,6 +96,12 @@ __device__ __forceinline__ void st(T *p, T val) {
 // for the 4-read/3-write stream: loads `nt`; stores `sc0 sc1 nt` (2-3 % above `nt` alone,
 // 9 % above default stores).
 #ifndef SWIFT_LOAD_AUX
+#ifndef SWIFT_COPY_U
+#define SWIFT_COPY_U 1                      // copy kernel: 16-byte vectors per lane
+#endif
+#ifndef SWIFT_COPY_WAVES_PER_CU
+#define SWIFT_COPY_WAVES_PER_CU 0           // copy kernel: residency cap (0 = none: measured best, 6.7 TB/s)
+#endif
 #define SWIFT_LOAD_AUX 2                // nt
 #endif
 #ifndef SWIFT_STORE_AUX
