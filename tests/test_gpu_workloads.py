@@ -190,6 +190,18 @@ def _selective_flow(B, synth, w, every):
     for k in off:
         for j in written:
             assert np.array_equal(mid[k][j].view(np.uint32), end[k][j].view(np.uint32))
+    # the benchmark's own selective undo: the mask comes back to the host, the grid covers the marked tensors only
+    B.swift_opt_step(tl, hp, host_mask=mask)
+    torch.cuda.synchronize()
+    again = _grab(s, picks)
+    B.swift_opt_undo(tl, hp, host_mask=dmask.cpu().tolist())
+    torch.cuda.synchronize()
+    back = _grab(s, picks)
+    _check_slices(w.kind, w.hyper, {k: again[k] for k in on}, {k: back[k] for k in on}, True, f"{w.name} host-mask undo")
+    for k in off:
+        for j in written:
+            assert np.array_equal(end[k][j].view(np.uint32), back[k][j].view(np.uint32))
+    end = back
     # and one full-list step + undo in the launch configuration the benchmark times
     B.swift_opt_step(tl, hp)
     torch.cuda.synchronize()
