@@ -151,6 +151,8 @@ def main() -> int:
         return 2
 
     import torch
+    from paper_2302_06173_amd import build as hip_build
+    hip_build.ensure_built()                      # loads what is built; builds only if there is no library
     from paper_2302_06173_amd import binding as B, synth
 
     if not torch.cuda.is_available():

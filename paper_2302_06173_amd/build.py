@@ -54,6 +54,16 @@ def build(force: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only if no library is there (tests, the smoke run and the benchmark call this; they never
+    rebuild what exists, so build again yourself after changing a source)."""
+    if not os.path.exists(LIB):
+        build()
+    elif not os.path.exists(EXAMPLE):
+        build_example()
+    return LIB
+
+
 def build_example() -> str:
     """The plain-C example program: gcc, linked against the library and the HIP runtime."""
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
