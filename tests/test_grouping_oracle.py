@@ -115,6 +115,8 @@ def test_special_cases():
     # for every pair, so singles pair up from the left before anything larger forms
     g = group_machines([1.0] * 8, [5.0] * 7, 1.0, math.inf, 5.0 * 3)[0]
     assert g == [[0, 1], [2, 3], [4, 5], [6, 7]]
+    # a tie goes to the pair with the lowest index (a reading: the paper does not say)
+    assert group_machines([1.0] * 4, [5.0] * 3, 1.0, math.inf, 10.0)[0] == [[0, 1], [2], [3]]
     # a link that carries nothing is never merged while merging elsewhere still frees storage
     g = group_machines([1.0, 1.0, 1.0], [0.0, 9.0], 1.0, 1.0, 1.0)[0]
     assert g == [[0], [1, 2]]

@@ -55,6 +55,7 @@ def test_identical_inputs_tie_to_the_lowest_index(B):
     got, _, _ = B.swift_logging_groups([1.0] * 8, [5.0] * 7, 1.0, math.inf, 15.0)
     assert got == [0, 0, 1, 1, 2, 2, 3, 3]
     assert got == _group_of(group_machines([1.0] * 8, [5.0] * 7, 1.0, math.inf, 15.0)[0])
+    assert B.swift_logging_groups([1.0] * 4, [5.0] * 3, 1.0, math.inf, 10.0)[0] == [0, 0, 1, 2]
 
 
 def test_argument_errors(B):
