@@ -134,7 +134,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_adamw")
-    ap.add_argument("--layout", default="by_tensor", choices=["by_tensor", "by_stream"],
+    ap.add_argument("--layout", default="by_tensor", choices=["by_tensor", "by_stream", "framework"],
                     help="where the state tensors are allocated: theta, g, m, v of a tensor side by side, "
                          "or all theta, then all g, all m, all v (same values either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -162,12 +162,14 @@ def make_state(w: Workload, device, shapes: Optional[Sequence[Shape]] = None, wi
 
     layout says where the tensors are allocated, not what they hold.  "by_tensor" (default): theta,
     g, m, v of one tensor next to each other, tensor after tensor.  "by_stream": every theta, then
-    every gradient, then every m, then every v.  Achieved HBM bandwidth depends on where the four
+    every gradient, then every m, then every v.  "framework": as a training framework allocates
+    (every theta when the model is built, gradients in backward order, then m and v of one tensor
+    after the other at the first optimizer step).  Achieved HBM bandwidth depends on where the four
     streams lie relative to each other (a few per cent either way, by workload), so benchmarks
     state the layout they used."""
     shapes = list(w.shapes if shapes is None else shapes)
     with_v = (w.kind != "sgdm") if with_v is None else with_v
-    if layout not in ("by_stream", "by_tensor"):
+    if layout not in ("by_stream", "by_tensor", "framework"):
         raise ValueError(f"unknown layout {layout!r}")
     dev = torch.device(device)
     gen = torch.Generator(device=dev)
@@ -180,6 +182,14 @@ def make_state(w: Workload, device, shapes: Optional[Sequence[Shape]] = None, wi
         gr = [new(n, gdt) for n in sizes]
         mo = [new(n) for n in sizes]
         vo = [new(n) for n in sizes] if with_v else None
+    elif layout == "framework":
+        th = [new(n) for n in sizes]                   # the model is built first,
+        gr = [new(n, gdt) for n in reversed(sizes)][::-1]   # gradients appear in backward order,
+        mo, vo = [], ([] if with_v else None)          # optimizer state tensor by tensor at the first step
+        for n in sizes:
+            mo.append(new(n))
+            if with_v:
+                vo.append(new(n))
     else:
         th, gr, mo, vo = [], [], [], ([] if with_v else None)
         for n in sizes:
