@@ -287,6 +287,22 @@ def main() -> int:
     extra("adamw_undo_bf16_copy", lambda: B.swift_opt_undo(tl_xb, hp_w), 26 + g_bytes)
     del xb, tl_xb
 
+    # the paper's own bookkeeping: the update launched group by group (here: about nine tensors per group, as
+    # gradients of one layer become final), every launch tracked, then the undo of whatever is marked
+    per_group = 9
+    ids = [list(range(k, min(k + per_group, n_t))) for k in range(0, n_t, per_group)]
+    groups = [B.TensorList([state.theta[i] for i in g], [state.grad[i] for i in g], [state.m[i] for i in g],
+                           [state.v[i] for i in g]) for g in ids]
+    tracker = B.Tracker(n_t)
+
+    def tracked_step_and_undo():
+        tracker.begin(t_step)
+        for g, tl_g in zip(ids, groups):
+            tracker.step(tl_g, g, hp_w)
+        tracker.undo(tl_adam, hp_w)
+    extra(f"adamw_tracked_step_in_{len(groups)}_groups_plus_undo", tracked_step_and_undo, 24 + g_bytes, 2 * N)
+    tracker.close()
+
     def masked_pair():
         B.swift_opt_step_dmask(tl_adam, hp_w, dmask)
         B.swift_opt_undo_dmask(tl_adam, hp_w, dmask)
