@@ -136,9 +136,38 @@ struct Plan {
 
 constexpr size_t kMaxPlans = 256;   // a layer-wise training loop keeps one plan per layer
 std::mutex g_plan_mu;
+// Keys are the caller's pointer and size arrays verbatim (hundreds of kilobytes for a list of ten thousand
+// tensors), compared in full on a hit.  Hashing all of that on every call would cost more than the comparison,
+// so the hash looks at the length, both ends and 32 evenly spaced words: lists that differ elsewhere only share
+// a bucket and are told apart by the comparison.
+struct KeyHash {
+  size_t operator()(const std::string &k) const noexcept {
+    const size_t n = k.size();
+    uint64_t h = 0x9E3779B97F4A7C15ull ^ (uint64_t)n;
+    auto mix = [&h](uint64_t v) {
+      h ^= v;
+      h *= 0xD6E8FEB86659FD93ull;
+      h ^= h >> 32;
+    };
+    auto word = [&k, n](size_t off) {
+      uint64_t v = 0;
+      memcpy(&v, k.data() + off, std::min<size_t>(8, n - off));
+      return v;
+    };
+    if (n <= 512) {
+      for (size_t off = 0; off < n; off += 8) mix(word(off));
+    } else {
+      for (size_t off = 0; off < 128; off += 8) mix(word(off));
+      for (size_t off = n - 128; off < n; off += 8) mix(word(off));
+      const size_t stride = (n / 32) & ~size_t(7);
+      for (size_t j = 1; j < 32; ++j) mix(word(j * stride));
+    }
+    return (size_t)h;
+  }
+};
 struct PlanCache {
   std::list<std::shared_ptr<Plan>> lru;                                               // most recently used first
-  std::unordered_map<std::string, std::list<std::shared_ptr<Plan>>::iterator> index;  // key -> position in lru
+  std::unordered_map<std::string, std::list<std::shared_ptr<Plan>>::iterator, KeyHash> index;  // key -> position in lru
 };
 PlanCache *g_plans = nullptr;   // leaked at exit on purpose: the HIP runtime may already be gone by then
 
@@ -339,26 +368,33 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
                    std::shared_ptr<Plan> *out) {
   const bool hasv = hp->kind != SWIFT_SGDM;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16;
-  std::string key;
-  key.reserve(64 + (size_t)l->n * 41);
-  key_add(key, (uint8_t)'O');
-  key_add(key, dev);
   const bool hasxb = l->param_bf16 != nullptr;
-  key_add(key, (uint8_t)hasv);
-  key_add(key, (uint8_t)bf16);
-  key_add(key, (uint8_t)hasxb);
-  key_add(key, l->n);
-  key_add(key, env_long("SWIFT_CHUNK_ELEMS", 0));
+  // header, then per tensor: numel, mask byte, the pointers (zero for an empty tensor, whose pointers are never read)
+  const size_t per_tensor = 8 + 1 + 8 * (3 + (hasv ? 1 : 0) + (hasxb ? 1 : 0));
+  std::string key(32 + (size_t)l->n * per_tensor, '\0');
+  char *kp = &key[0];
+  auto put = [&kp](const auto &v) {
+    memcpy(kp, &v, sizeof v);
+    kp += sizeof v;
+  };
+  put((uint8_t)'O');
+  put((uint8_t)hasv);
+  put((uint8_t)bf16);
+  put((uint8_t)hasxb);
+  put((int32_t)dev);
+  put((int64_t)l->n);
+  put((int64_t)env_long("SWIFT_CHUNK_ELEMS", 0));
+  kp = &key[32];
   for (int64_t i = 0; i < l->n; ++i) {
-    const uint8_t on = host_mask ? (host_mask[i] != 0) : 1;
-    key_add(key, l->numel[i]);
-    key_add(key, on);
-    if (l->numel[i] == 0) continue;
-    key_add(key, l->param[i]);
-    key_add(key, l->grad[i]);
-    key_add(key, l->m[i]);
-    if (hasv) key_add(key, l->v[i]);
-    if (hasxb) key_add(key, l->param_bf16[i]);
+    const int64_t n = l->numel[i];
+    put(n);
+    put((uint8_t)(host_mask ? (host_mask[i] != 0) : 1));
+    const bool live = n != 0;
+    put(live ? (const void *)l->param[i] : nullptr);
+    put(live ? l->grad[i] : nullptr);
+    put(live ? (const void *)l->m[i] : nullptr);
+    if (hasv) put(live ? (const void *)l->v[i] : nullptr);
+    if (hasxb) put(live ? (const void *)l->param_bf16[i] : nullptr);
   }
   if (auto hit = find_plan(key)) {
     *out = hit;
