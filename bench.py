@@ -295,12 +295,14 @@ def main() -> int:
                            [state.v[i] for i in g]) for g in ids]
     tracker = B.Tracker(n_t)
 
+    hp_a = hps["adam"]       # Adam, not AdamW: the roofline kernel's launches stay those of the timed pass
+
     def tracked_step_and_undo():
         tracker.begin(t_step)
         for g, tl_g in zip(ids, groups):
-            tracker.step(tl_g, g, hp_w)
-        tracker.undo(tl_adam, hp_w)
-    extra(f"adamw_tracked_step_in_{len(groups)}_groups_plus_undo", tracked_step_and_undo, 24 + g_bytes, 2 * N)
+            tracker.step(tl_g, g, hp_a)
+        tracker.undo(tl_adam, hp_a)
+    extra(f"adam_tracked_step_in_{len(groups)}_groups_plus_undo", tracked_step_and_undo, 24 + g_bytes, 2 * N)
     tracker.close()
 
     def masked_pair():
