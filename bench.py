@@ -134,9 +134,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_adamw")
-    ap.add_argument("--layout", default="by_tensor", choices=["by_tensor", "by_stream", "framework"],
-                    help="where the state tensors are allocated: theta, g, m, v of a tensor side by side, "
-                         "or all theta, then all g, all m, all v (same values either way)")
+    ap.add_argument("--layout", default="padded", choices=["padded", "by_tensor", "by_stream", "framework"],
+                    help="where the state tensors are allocated (same values either way): one arena with theta, g, m, v "
+                         "of a tensor side by side and 4 KiB of skew between buffers (default); the same order in "
+                         "separate torch allocations; all theta, then all g, m, v; or as a training framework would")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the launches reported under 'extras' (a profile of such a run holds the timed pass only)")

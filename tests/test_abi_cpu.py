@@ -171,6 +171,26 @@ def test_synthetic_workloads_have_the_stated_sizes():
     assert sum(mask) == 146 and mask == synth.tensor_mask(w["llama7b_adamw"], 291)
 
 
+def test_padded_layout_keeps_values_and_skews_the_buffers():
+    import torch
+    from paper_2302_06173_amd import synth
+    for nbytes in (1 << 20, (1 << 20) + 4, 4 << 20, 30_720_000, 64 << 20, 180_355_072, 524_288_000):
+        d = synth.padded_extent(nbytes)
+        assert d >= nbytes + 4096 and d % 8192 == 4096          # never a multiple of 8 KiB apart
+        assert d - nbytes <= nbytes // 16 + 65536 + 4096          # little memory given away
+    assert synth.padded_extent(100) == 256 and synth.padded_extent(0) == 0
+    w = synth.workloads()["gpt2_xl_adamw_bf16g"]
+    shapes = [(33,), (0,), (5,), (300_000,), (70_001,)]
+    ref = synth.make_state(w, "cpu", shapes=shapes, layout="by_tensor")
+    for layout in ("padded", "by_stream", "framework"):
+        s = synth.make_state(w, "cpu", shapes=shapes, layout=layout)
+        for a, b in zip((s.theta, s.grad, s.m, s.v), (ref.theta, ref.grad, ref.m, ref.v)):
+            assert all(torch.equal(x, y) and x.dtype == y.dtype for x, y in zip(a, b)), layout
+    s = synth.make_state(w, "cpu", shapes=shapes)                 # the default is the padded arena
+    assert s.grad[3].data_ptr() - s.theta[3].data_ptr() == synth.padded_extent(300_000 * 4)
+    assert all(t.data_ptr() % 16 == 0 for t in s.theta + s.m + s.v if t.numel())
+
+
 def test_tracker_host_logic_without_a_gpu(B):
     h = ctypes.c_void_p()
     assert B._lib.swift_tracker_create(-1, ctypes.byref(h)) == B.SWIFT_EINVAL
