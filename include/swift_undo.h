@@ -92,9 +92,9 @@ typedef struct {
  * (8-byte for bfloat16 buffers) selects the 128-bit access path; results are bit-identical either way.
  * v may be NULL for SWIFT_SGDM.  Tensors with numel 0 are allowed and skipped.
  * Placement advice (throughput only, never correctness): on MI355X the kernels run 2-10 % faster when
- * param[i], grad[i], m[i], v[i] of a tensor do NOT start a multiple of 8 KiB apart, e.g. when consecutive
- * buffers of an arena are an odd multiple of 4 KiB apart; allocators that hand out buffers at 2 MiB
- * granularity produce the slow case.
+ * param[i], grad[i], m[i], v[i] of a tensor do NOT all start at the same address modulo 8 KiB, e.g. when
+ * consecutive buffers of an arena are an odd multiple of 4 KiB apart; allocators that hand out buffers at
+ * 2 MiB granularity produce the slow case.
  * param_bf16 (nullable array; not from the paper): mixed-precision training keeps a bfloat16 copy of
  * the parameters next to the binary32 master weights.  If the array is given, swift_opt_step and
  * swift_opt_undo (host- and device-mask forms) also write, for every tensor they touch, the bfloat16

@@ -145,9 +145,10 @@ def workloads() -> dict:
 def padded_extent(nbytes: int) -> int:
     """Bytes from the start of one buffer to the start of the next in the "padded" layout: the size
     rounded up to a power-of-two granule of at most 1/16 of the buffer (64 KiB .. 2 MiB), plus 4 KiB.
-    The streams of a tensor then never lie a multiple of 8 KiB apart, the distance at which the
-    memory system serves the same tile of all four streams from the same channel (measured: 5-10 %
-    slower for tensors of a few MiB, 2-3 % for the 7B list).  Small buffers are only rounded to 256 B."""
+    Consecutive buffers are then an odd multiple of 4 KiB apart, so theta, g, m, v of a tensor do not
+    all start at the same address modulo 8 KiB -- the placement in which the memory system serves the
+    same tile of all four streams from the same place (measured: 5-10 % slower for tensors of a few
+    MiB, 2-3 % for the 7B list).  Small buffers are only rounded to 256 B."""
     if nbytes < (1 << 20):
         return (nbytes + 255) // 256 * 256
     granule = 1 << 16
