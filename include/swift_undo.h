@@ -93,7 +93,7 @@ typedef struct {
  * v may be NULL for SWIFT_SGDM.  Tensors with numel 0 are allowed and skipped.
  * Placement advice (throughput only, never correctness): on MI355X the kernels run 2-10 % faster when
  * param[i], grad[i], m[i], v[i] of a tensor do NOT all start at the same address modulo 8 KiB, e.g. when
- * consecutive buffers of an arena are an odd multiple of 4 KiB apart; allocators that hand out buffers at
+ * consecutive buffers of an arena are an odd multiple of 2 KiB apart; allocators that hand out buffers at
  * 2 MiB granularity produce the slow case.
  * param_bf16 (nullable array; not from the paper): mixed-precision training keeps a bfloat16 copy of
  * the parameters next to the binary32 master weights.  If the array is given, swift_opt_step and

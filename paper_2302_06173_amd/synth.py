@@ -144,17 +144,14 @@ def workloads() -> dict:
 
 def padded_extent(nbytes: int) -> int:
     """Bytes from the start of one buffer to the start of the next in the "padded" layout: the size
-    rounded up to a power-of-two granule of at most 1/16 of the buffer (64 KiB .. 2 MiB), plus 4 KiB.
-    Consecutive buffers are then an odd multiple of 4 KiB apart, so theta, g, m, v of a tensor do not
-    all start at the same address modulo 8 KiB -- the placement in which the memory system serves the
-    same tile of all four streams from the same place (measured: 5-10 % slower for tensors of a few
-    MiB, 2-3 % for the 7B list).  Small buffers are only rounded to 256 B."""
+    rounded up to 8 KiB, plus 2 KiB.  Consecutive buffers are then an odd multiple of 2 KiB apart, so
+    theta, g, m, v of a tensor start in four different quarters of an 8 KiB window instead of at the
+    same address modulo 8 KiB -- the placement in which the memory system serves the same tile of all
+    four streams from the same place (measured: 5-10 % slower for tensors of a few MiB, 2-3 % for the
+    7B list).  Buffers under 1 MiB are only rounded to 256 B."""
     if nbytes < (1 << 20):
         return (nbytes + 255) // 256 * 256
-    granule = 1 << 16
-    while granule < (1 << 21) and granule * 2 <= nbytes // 16:
-        granule *= 2
-    return (nbytes + granule - 1) // granule * granule + 4096
+    return (nbytes + 8191) // 8192 * 8192 + 2048
 
 
 @dataclass
@@ -177,7 +174,7 @@ def make_state(w: Workload, device, shapes: Optional[Sequence[Shape]] = None, wi
 
     layout says where the tensors are allocated, not what they hold.
       "padded" (default): one arena, theta, g, m, v of a tensor next to each other, tensor after tensor,
-          consecutive buffers padded_extent() apart;
+          consecutive buffers padded_extent() apart (an odd multiple of 2 KiB);
       "by_tensor": the same order, every buffer an allocation of its own (torch's caching allocator);
       "by_stream": every theta, then every gradient, then every m, then every v;
       "framework": as a training framework allocates (every theta when the model is built, gradients
