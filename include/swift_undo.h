@@ -10,16 +10,33 @@
  * General rules
  *   - Plain C types only.  Every pointer is marked HOST or DEVICE below.  DEVICE pointers must
  *     be ordinary device allocations of the GPU that is current (hipSetDevice) during the call.
- *   - The caller owns every buffer it passes.  The library allocates only small internal tables
- *     (tensor descriptors and chunk lists, cached per distinct tensor list), which it frees in
- *     swift_shutdown() or when the process ends.
+ *   - The caller owns every buffer it passes.  The library allocates only internal tables (tensor
+ *     descriptors and chunk lists, 64 bytes per 16 Ki or 64 Ki elements, plus the per-list scratch the
+ *     LAMB, fused-digest and device-mask calls describe), cached per distinct tensor list -- distinct
+ *     meaning: same pointers, sizes, gradient type and host mask.  The first call on a list builds its
+ *     tables (an allocation and synchronous copies: about 2 ms for a few hundred tensors); later calls
+ *     find them.  Tables are NEVER freed as a side effect of another call: only swift_cache_trim (the
+ *     caller decides when) and swift_shutdown free them.  swift_cache_stats tells how much is held.
+ *   - HIP graphs: a call on a list whose tables exist consists of kernel launches only and may be
+ *     captured.  A call that would have to build tables (a list, or a kind of call on it, that has not
+ *     been made before) while its stream is capturing returns SWIFT_EINVAL: make the same call once
+ *     before the capture.  A captured graph holds pointers into the tables it was recorded with; such
+ *     tables survive swift_cache_trim, and swift_shutdown must not be called while a graph that was
+ *     captured over library calls may still be replayed.
+ *   - Pointer checks (device memory of the current GPU, numel elements inside one allocation, no
+ *     overlap) are made in full when a list's tables are built.  Later calls on the same list look up
+ *     its first buffer again and rebuild the tables if the allocation behind it has changed; a caller
+ *     that frees tensors and allocates others at the same addresses gets no further checking.
  *   - HOST arrays (pointer arrays, numel, masks, hyper-parameters) are read during the call only.
  *   - Work is enqueued on `hip_stream` (a hipStream_t; NULL = the default stream) and the call
  *     returns without waiting for it.  Order with respect to other work -- including update
  *     kernels that were launched before a failure was noticed and must still run to completion
  *     (paper, Implementation, "Update-undo") -- is stream order.
- *   - Every entry point returns SWIFT_OK (0) or a negative swift_status.  On error nothing has
- *     been enqueued and swift_last_error() describes the problem.  No exceptions, no aborts.
+ *   - Every entry point returns SWIFT_OK (0) or a negative swift_status and swift_last_error()
+ *     describes the problem.  No exceptions, no aborts.  SWIFT_EINVAL and SWIFT_ENOTINVERTIBLE are
+ *     reported before anything is enqueued.  SWIFT_EHIP from a kernel launch can leave earlier
+ *     launches of the same call on the stream (the LAMB step, the fused-digest and the device-mask
+ *     calls are two or three launches): the state is then undefined, as after any failed launch.
  *   - theta, m and v are IEEE binary32; gradients are binary32 or bfloat16.  Arithmetic inside
  *     the kernels is binary64 with one rounding to binary32 at each store.  NaN/Inf propagate;
  *     denormals are kept; nothing is clamped.
@@ -262,7 +279,18 @@ int swift_logging_groups(int64_t n_machines, const double *compute_time, const d
                          double checkpoint_interval, double bandwidth, double storage_limit, int parallel_recovery,
                          int32_t *group_of, double *storage_out, double *recovery_out);
 
-/* Frees every cached table on every device (synchronises those devices first). */
+/* What the library holds: number of cached lists and bytes of device memory behind them (either
+ * pointer may be NULL).  HOST. */
+int swift_cache_stats(int64_t *n_lists, int64_t *device_bytes);
+
+/* Frees cached tables, least recently used first, until at most max_device_bytes remain (0: all that
+ * can go).  Tables that a captured graph may use are kept.  Freeing synchronises the device.  The
+ * only call besides swift_shutdown that frees tables: a training loop whose lists keep changing
+ * (fresh host masks, re-allocated tensors) calls it when it sees fit. */
+int swift_cache_trim(int64_t max_device_bytes);
+
+/* Frees every cached table on every device (synchronises those devices first), including tables that
+ * captured graphs use: do not replay such graphs afterwards. */
 int swift_shutdown(void);
 
 /* Message of the last error on the calling thread ("" if none).  HOST, owned by the library. */

@@ -67,12 +67,17 @@ _lib.swift_tracker_undo.argtypes = [_P, ctypes.POINTER(SwiftTensorList), ctypes.
 _lib.swift_tracker_destroy.argtypes = [_P]
 for _name in ("create", "begin", "step", "marks", "undo", "destroy"):
     getattr(_lib, "swift_tracker_" + _name).restype = ctypes.c_int
+_lib.swift_cache_stats.argtypes = [ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+_lib.swift_cache_stats.restype = ctypes.c_int
+_lib.swift_cache_trim.argtypes = [ctypes.c_int64]
+_lib.swift_cache_trim.restype = ctypes.c_int
 _lib.swift_shutdown.argtypes = []
 _lib.swift_shutdown.restype = ctypes.c_int
 _lib.swift_last_error.argtypes = []
 _lib.swift_last_error.restype = ctypes.c_char_p
 
 EXPORTS = ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask",
+           "swift_cache_stats", "swift_cache_trim",
            "swift_lamb_step", "swift_lamb_undo", "swift_opt_step_digest", "swift_opt_undo_digest",
            "swift_tracker_create", "swift_tracker_begin", "swift_tracker_step", "swift_tracker_marks",
            "swift_tracker_undo", "swift_tracker_destroy",
@@ -369,6 +374,17 @@ def swift_logging_groups(compute_time: Sequence[float], message_bytes: Sequence[
     _check(_lib.swift_logging_groups(n, R, M, float(checkpoint_interval), float(bandwidth), float(storage_limit),
                                      1 if parallel_recovery else 0, out, ctypes.byref(storage), ctypes.byref(recovery)))
     return list(out[:n]), storage.value, recovery.value
+
+
+def swift_cache_stats():
+    """(number of cached lists, bytes of device memory behind them)."""
+    n, b = ctypes.c_int64(), ctypes.c_int64()
+    _check(_lib.swift_cache_stats(ctypes.byref(n), ctypes.byref(b)))
+    return n.value, b.value
+
+
+def swift_cache_trim(max_device_bytes: int = 0) -> None:
+    _check(_lib.swift_cache_trim(int(max_device_bytes)))
 
 
 def swift_shutdown() -> None:

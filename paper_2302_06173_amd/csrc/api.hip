@@ -67,6 +67,41 @@ long env_long(const char *name, long dflt) {
   return (end && *end == 0) ? v : dflt;
 }
 
+// Tuning knobs.  They exist for sweeps: the defaults are the measured best.  The environment is read
+// once, when the first call needs a knob; only a process started with SWIFT_TUNE=1 reads it again on
+// every call (a sweep that changes the variables between calls).  kUnset = "use the built-in default".
+constexpr long kUnset = -1;
+struct Knobs {
+  long tile_u, tile_block, waves_per_cu, chunk_elems, dmask_wgs_per_cu;
+  long digest_chunk_elems, copy_u, copy_waves_per_cu;
+  long lamb_u1, lamb_u3, lamb_waves_p1, lamb_waves_p3, fused_u, fused_waves_per_cu;
+};
+
+Knobs read_knobs() {
+  Knobs k;
+  k.tile_u = env_long("SWIFT_TILE_U", SWIFT_DEFAULT_U);
+  k.tile_block = env_long("SWIFT_TILE_BLOCK", SWIFT_DEFAULT_BLOCK);
+  k.waves_per_cu = env_long("SWIFT_WAVES_PER_CU", kUnset);
+  k.chunk_elems = env_long("SWIFT_CHUNK_ELEMS", 0);
+  k.dmask_wgs_per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
+  k.digest_chunk_elems = env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0);
+  k.copy_u = env_long("SWIFT_COPY_U", SWIFT_COPY_U);
+  k.copy_waves_per_cu = env_long("SWIFT_COPY_WAVES_PER_CU", SWIFT_COPY_WAVES_PER_CU);
+  k.lamb_u1 = env_long("SWIFT_LAMB_U1", SWIFT_LAMB_U1);
+  k.lamb_u3 = env_long("SWIFT_LAMB_U3", SWIFT_LAMB_U3);
+  k.lamb_waves_p1 = env_long("SWIFT_LAMB_WAVES_P1", SWIFT_LAMB_WAVES_P1);
+  k.lamb_waves_p3 = env_long("SWIFT_LAMB_WAVES_P3", SWIFT_LAMB_WAVES_P3);
+  k.fused_u = env_long("SWIFT_FUSED_U", SWIFT_FUSED_U);
+  k.fused_waves_per_cu = env_long("SWIFT_FUSED_WAVES_PER_CU", SWIFT_FUSED_WAVES_PER_CU);
+  return k;
+}
+
+Knobs knobs() {
+  static const bool live = env_long("SWIFT_TUNE", 0) != 0;
+  static const Knobs at_start = read_knobs();
+  return live ? read_knobs() : at_start;
+}
+
 // ------------------------------------------------------------------------------------------
 // Device facts, queried once per device.
 struct DeviceInfo {
@@ -103,6 +138,11 @@ struct Plan {
   uint32_t n_chunks = 0;
   uint32_t chunk_elems = 0;
   uint64_t n_out = 0;            // digest plans: number of outputs
+  size_t dev_bytes = 0;          // device memory held by this plan (tables and scratch)
+  bool pinned = false;           // used while a stream was capturing: a graph may replay it, never trimmed
+  const void *probe_ptr = nullptr;   // first buffer of the list and the allocation it was found in when the
+  const void *probe_base = nullptr;  // plan was built: looked up again on every later use (guarded by g_plan_mu)
+  size_t probe_size = 0;
   // optimizer plans: where each tensor of the caller's list sits in the chunk table
   std::vector<uint64_t> t_first_chunk, t_numel;   // t_numel[i] = 0 for empty or unmarked tensors
   std::vector<uint8_t> t_active;
@@ -111,9 +151,11 @@ struct Plan {
   void *lamb_spans = nullptr;
   void *lamb_partial = nullptr;
   uint32_t lamb_tile_elems = 0;
-  // fused step/undo + digest only, created on first use (guarded by lamb_mu): chunk spans and slots
+  // fused step/undo + digest only, created on first use (guarded by lamb_mu): chunk spans, chunk sums, tile sums
   void *fused_spans = nullptr;
   void *fused_slots = nullptr;
+  void *fused_tiles = nullptr;
+  uint32_t fused_tile_elems = 0;
   // device-mask calls only, created on first use (guarded by lamb_mu): [tensor spans | packed chunk table | slot count]
   void *packed_mem = nullptr;
   size_t packed_table_off = 0, packed_count_off = 0;
@@ -128,13 +170,17 @@ struct Plan {
       if (lamb_partial) (void)hipFree(lamb_partial);
       if (fused_spans) (void)hipFree(fused_spans);
       if (fused_slots) (void)hipFree(fused_slots);
+      if (fused_tiles) (void)hipFree(fused_tiles);
       if (packed_mem) (void)hipFree(packed_mem);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     }
   }
 };
 
-constexpr size_t kMaxPlans = 256;   // a layer-wise training loop keeps one plan per layer
+// The cache only grows: tables are freed by swift_cache_trim (the caller's decision) and by
+// swift_shutdown, never as a side effect of another call.  A captured graph holds raw pointers into a
+// plan's tables and scratch, so a plan that was used while its stream was capturing is pinned and
+// survives every trim.
 std::mutex g_plan_mu;
 // Keys are the caller's pointer and size arrays verbatim (hundreds of kilobytes for a list of ten thousand
 // tensors), compared in full on a hit.  Hashing all of that on every call would cost more than the comparison,
@@ -192,10 +238,82 @@ void keep_plan(const std::shared_ptr<Plan> &p) {
   }
   g_plans->lru.push_front(p);
   g_plans->index[p->key] = g_plans->lru.begin();
-  if (g_plans->lru.size() > kMaxPlans) {        // cannot coincide with the replacement above: that kept the size
-    dropped = g_plans->lru.back();
-    g_plans->index.erase(dropped->key);
-    g_plans->lru.pop_back();
+}
+
+// Takes one plan out of the cache (its tables are freed when the last reference goes).
+void drop_plan(const std::shared_ptr<Plan> &p) {
+  std::lock_guard<std::mutex> lock(g_plan_mu);
+  if (!g_plans) return;
+  auto hit = g_plans->index.find(p->key);
+  if (hit == g_plans->index.end() || *hit->second != p) return;
+  g_plans->lru.erase(hit->second);
+  g_plans->index.erase(hit);
+}
+
+// Is `stream` recording a graph right now?  (The legacy default stream cannot.)
+int stream_is_capturing(hipStream_t stream, bool *capturing) {
+  *capturing = false;
+  if (!stream) return SWIFT_OK;
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  SWIFT_HIP(hipStreamIsCapturing(stream, &st));
+  *capturing = st != hipStreamCaptureStatusNone;
+  return SWIFT_OK;
+}
+
+// The library may not allocate or copy synchronously while the caller's stream records a graph:
+// whatever a call needs must exist before the capture begins.
+int refuse_under_capture(hipStream_t stream, const char *what) {
+  bool capturing = false;
+  int rc = stream_is_capturing(stream, &capturing);
+  if (rc) return rc;
+  if (capturing)
+    return fail(SWIFT_EINVAL, "the stream is capturing a graph and %s: make the same call once before the capture begins, "
+                              "so that the library's tables for this tensor list exist", what);
+  return SWIFT_OK;
+}
+
+// A cached plan is about to be used on `stream`.  It is pinned if the stream is capturing.  The first
+// buffer of the list is looked up again: if the runtime no longer knows it, or finds it in another
+// allocation than when the plan was built, the caller has freed and re-allocated its tensors, the
+// cached validation is void and the plan is dropped (*stale = true; the caller rebuilds it).
+int reuse_plan(const std::shared_ptr<Plan> &plan, hipStream_t stream, bool *stale) {
+  *stale = false;
+  if (plan->probe_ptr) {
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    const hipError_t e = hipMemGetAddressRange(&base, &size, const_cast<void *>(plan->probe_ptr));
+    if (e != hipSuccess) (void)hipGetLastError();
+    if (e != hipSuccess || base != plan->probe_base || size != plan->probe_size) {
+      if (plan->pinned)
+        return fail(SWIFT_EINVAL, "the tensors of a list that a captured graph uses were re-allocated");
+      int rc = refuse_under_capture(stream, "the cached tables of this list are stale (its tensors were re-allocated)");
+      if (rc) return rc;
+      drop_plan(plan);
+      *stale = true;
+      return SWIFT_OK;
+    }
+  }
+  if (!plan->pinned) {
+    bool capturing = false;
+    int rc = stream_is_capturing(stream, &capturing);
+    if (rc) return rc;
+    if (capturing) {
+      std::lock_guard<std::mutex> lock(g_plan_mu);
+      plan->pinned = true;
+    }
+  }
+  return SWIFT_OK;
+}
+
+void set_probe(Plan &plan, const void *p) {
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  if (p && hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) == hipSuccess) {
+    plan.probe_ptr = p;
+    plan.probe_base = base;
+    plan.probe_size = size;
+  } else {
+    (void)hipGetLastError();
   }
 }
 
@@ -247,11 +365,8 @@ Tuning opt_tuning(int kind, bool bf16) {
   // 4 and 3; bf16 gradients halve one stream), the more wavefronts a compute unit wants.
   const int waves = kind == SWIFT_SGDM ? (bf16 ? SWIFT_DEFAULT_WAVES_PER_CU_SGDM + 1 : SWIFT_DEFAULT_WAVES_PER_CU_SGDM)
                                        : (bf16 ? SWIFT_DEFAULT_WAVES_PER_CU + 1 : SWIFT_DEFAULT_WAVES_PER_CU);
-  Tuning t{SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK, waves};
-  t.u = (int)env_long("SWIFT_TILE_U", t.u);
-  t.block = (int)env_long("SWIFT_TILE_BLOCK", t.block);
-  t.waves_per_cu = (int)env_long("SWIFT_WAVES_PER_CU", t.waves_per_cu);
-  return t;
+  const Knobs k = knobs();
+  return Tuning{(int)k.tile_u, (int)k.tile_block, k.waves_per_cu == kUnset ? waves : (int)k.waves_per_cu};
 }
 
 // Dynamic LDS bytes per workgroup that make at most waves_per_cu wavefronts fit on one CU.
@@ -268,9 +383,15 @@ uint32_t lds_cap_bytes(const DeviceInfo &info, const Tuning &t) {
 // tensors of a small model.
 constexpr uint32_t kMaxTileElems = 4096;
 uint32_t pick_chunk_elems(uint64_t total_elems) {
-  long forced = env_long("SWIFT_CHUNK_ELEMS", 0);              // tuning knob for sweeps
+  const long forced = knobs().chunk_elems;                     // tuning knob for sweeps
   if (forced >= (long)kMaxTileElems && forced <= (1l << 22) && (forced & (forced - 1)) == 0) return (uint32_t)forced;
   return total_elems >= (1ull << 28) ? 65536u : 16384u;
+}
+
+uint32_t shift_for(uint32_t tile_elems, uint32_t chunk_elems) {
+  uint32_t s = 0;
+  while ((tile_elems << s) < chunk_elems) ++s;
+  return s;
 }
 
 int upload_plan(Plan &plan, const void *descs, size_t desc_bytes, const void *chunks, size_t n_chunks,
@@ -278,6 +399,7 @@ int upload_plan(Plan &plan, const void *descs, size_t desc_bytes, const void *ch
   plan.desc_bytes = (desc_bytes + 255) & ~size_t(255);
   const size_t total = plan.desc_bytes + std::max<size_t>(n_chunks, 1) * chunk_size;
   SWIFT_HIP(hipMalloc(&plan.dev_mem, total));
+  plan.dev_bytes += total;
   // Synchronous copies: when they return the table is complete in device memory, so any stream
   // may read it.  This happens once per distinct tensor list.
   if (desc_bytes) SWIFT_HIP(hipMemcpy(plan.dev_mem, descs, desc_bytes, hipMemcpyHostToDevice));
@@ -294,6 +416,26 @@ struct Interval {
   uintptr_t lo, hi;
   bool written;
 };
+
+// Sorts the ranges by start address and checks that nothing that is written overlaps anything else.
+// In order of start address, a range overlaps an earlier one iff it starts below the furthest end seen
+// so far; gradients (read only) may overlap each other.
+int check_no_overlap(Interval *iv, size_t n) {
+  std::sort(iv, iv + n, [](const Interval &a, const Interval &b) { return a.lo < b.lo; });
+  const Interval *far_any = nullptr, *far_written = nullptr;
+  for (size_t k = 0; k < n; ++k) {
+    const Interval &cur = iv[k];
+    const Interval *hit = nullptr;
+    if (far_written && cur.lo < far_written->hi) hit = far_written;
+    else if (cur.written && far_any && cur.lo < far_any->hi) hit = far_any;
+    if (hit)
+      return fail(SWIFT_EINVAL, "buffers overlap: [%p, %p) and [%p, %p)", (void *)hit->lo, (void *)hit->hi, (void *)cur.lo,
+                  (void *)cur.hi);
+    if (!far_any || cur.hi > far_any->hi) far_any = &cur;
+    if (cur.written && (!far_written || cur.hi > far_written->hi)) far_written = &cur;
+  }
+  return SWIFT_OK;
+}
 
 int validate_hparams(const swift_hparams *hp, bool undo, OptConsts *c) {
   if (!hp) return fail(SWIFT_EINVAL, "hparams is NULL");
@@ -365,7 +507,7 @@ int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
 }
 
 int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, int dev,
-                   std::shared_ptr<Plan> *out) {
+                   hipStream_t stream, std::shared_ptr<Plan> *out) {
   const bool hasv = hp->kind != SWIFT_SGDM;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16;
   const bool hasxb = l->param_bf16 != nullptr;
@@ -383,7 +525,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   put((uint8_t)hasxb);
   put((int32_t)dev);
   put((int64_t)l->n);
-  put((int64_t)env_long("SWIFT_CHUNK_ELEMS", 0));
+  put((int64_t)knobs().chunk_elems);
   kp = &key[32];
   for (int64_t i = 0; i < l->n; ++i) {
     const int64_t n = l->numel[i];
@@ -397,12 +539,22 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     if (hasxb) put(live ? (const void *)l->param_bf16[i] : nullptr);
   }
   if (auto hit = find_plan(key)) {
-    *out = hit;
-    return SWIFT_OK;
+    bool stale = false;
+    int rc = reuse_plan(hit, stream, &stale);
+    if (rc) return rc;
+    if (!stale) {
+      *out = hit;
+      return SWIFT_OK;
+    }
   }
 
   // Miss: check every pointer against the runtime's allocation records, check that nothing that
-  // is written overlaps anything else, then build and upload the chunk table.
+  // is written overlaps anything else, then build and upload the chunk table (an allocation and
+  // synchronous copies: not while the stream records a graph).
+  {
+    int rc = refuse_under_capture(stream, "this tensor list has not been used before");
+    if (rc) return rc;
+  }
   std::vector<Interval> iv;
   iv.reserve((size_t)l->n * 4);
   uint64_t total = 0;
@@ -424,20 +576,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     if (hasv) iv.push_back({(uintptr_t)l->v[i], (uintptr_t)l->v[i] + n * 4, true});
     if (!host_mask || host_mask[i]) total += n;
   }
-  std::sort(iv.begin(), iv.end(), [](const Interval &a, const Interval &b) { return a.lo < b.lo; });
-  // In order of start address, a range overlaps an earlier one iff it starts below the furthest end seen so
-  // far; gradients (read only) may overlap each other, anything that is written may overlap nothing.
-  const Interval *far_any = nullptr, *far_written = nullptr;
-  for (const Interval &cur : iv) {
-    const Interval *hit = nullptr;
-    if (far_written && cur.lo < far_written->hi) hit = far_written;
-    else if (cur.written && far_any && cur.lo < far_any->hi) hit = far_any;
-    if (hit)
-      return fail(SWIFT_EINVAL, "buffers overlap: [%p, %p) and [%p, %p)", (void *)hit->lo, (void *)hit->hi, (void *)cur.lo,
-                  (void *)cur.hi);
-    if (!far_any || cur.hi > far_any->hi) far_any = &cur;
-    if (cur.written && (!far_written || cur.hi > far_written->hi)) far_written = &cur;
-  }
+  if (int rc = check_no_overlap(iv.data(), iv.size())) return rc;
 
   auto plan = std::make_shared<Plan>();
   plan->key = std::move(key);
@@ -480,6 +619,8 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
   if (chunks.size() > 0x7fffffffull) return fail(SWIFT_EINVAL, "tensor list is too large");
   int rc = upload_plan(*plan, nullptr, 0, chunks.data(), chunks.size(), sizeof(ChunkDesc));
   if (rc) return rc;
+  for (int64_t i = 0; i < l->n && !plan->probe_ptr; ++i)
+    if (l->numel[i] > 0) set_probe(*plan, l->param[i]);
   keep_plan(plan);
   *out = plan;
   return SWIFT_OK;
@@ -523,9 +664,10 @@ OptPackedKernel pick_packed_kernel(int kind, bool undo, bool bf16, bool xb) {
 
 // Scratch of the device-mask calls: where each tensor's chunks sit, room for the packed table and
 // its slot count.  Calls that share a plan (the same tensors) share it, like the tensors themselves.
-int packed_prepare(Plan &plan) {
+int packed_prepare(Plan &plan, hipStream_t stream) {
   std::lock_guard<std::mutex> lock(plan.lamb_mu);
   if (plan.packed_mem) return SWIFT_OK;
+  if (int rc = refuse_under_capture(stream, "this tensor list has not been used with a device mask before")) return rc;
   std::vector<TensorChunks> spans(plan.t_numel.size());
   for (size_t i = 0; i < spans.size(); ++i) {
     spans[i].first = (uint32_t)plan.t_first_chunk[i];
@@ -543,13 +685,29 @@ int packed_prepare(Plan &plan) {
   plan.packed_table_off = table_off;
   plan.packed_count_off = count_off;
   plan.packed_mem = mem;
+  plan.dev_bytes += count_off + 256;
   return SWIFT_OK;
 }
 
-int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask,
-             const uint8_t *device_mask, bool want_dmask, bool undo, void *stream_) {
+// An optimizer call in two halves: everything that can fail for a reason of the caller's making
+// (arguments, pointers, tables) happens in opt_prepare, which enqueues nothing; opt_launch then
+// enqueues the kernels.  The tracker puts its stream wait between the two.
+struct OptLaunch {
   OptConsts c;
-  int rc = validate_hparams(hp, undo, &c);
+  DeviceInfo info;
+  Tuning tune;
+  OptKernel kernel = nullptr;
+  OptPackedKernel packed_kernel = nullptr;
+  std::shared_ptr<Plan> plan;
+  const uint8_t *device_mask = nullptr;
+  uint32_t n_tensors = 0, tpc_shift = 0;
+  uint64_t n_slots = 0;
+  bool empty = true;               // nothing to launch
+};
+
+int opt_prepare(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask,
+                const uint8_t *device_mask, bool want_dmask, bool undo, hipStream_t stream, OptLaunch *out) {
+  int rc = validate_hparams(hp, undo, &out->c);
   if (rc) return rc;
   if (hp->kind == SWIFT_LAMB)
     return fail(SWIFT_EINVAL, "LAMB needs the saved norms: use swift_lamb_step / swift_lamb_undo");
@@ -558,26 +716,36 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   if (l->n == 0) return SWIFT_OK;
   int dev = -1;
   SWIFT_HIP(hipGetDevice(&dev));
-  DeviceInfo info;
-  if ((rc = device_info(dev, &info))) return rc;
+  if ((rc = device_info(dev, &out->info))) return rc;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16, xb = l->param_bf16 != nullptr;
-  Tuning tune = opt_tuning(hp->kind, bf16);
-  if (want_dmask) tune.u = SWIFT_DEFAULT_U, tune.block = SWIFT_DEFAULT_BLOCK;     // the only packed-table shape
-  const OptKernel kernel = pick_kernel(tune, hp->kind, undo, bf16, xb);
-  if (!kernel) return fail(SWIFT_EINVAL, "launch shape U=%d BLOCK=%d is not compiled in", tune.u, tune.block);
-  const uint32_t tile_elems = (uint32_t)tune.u * (uint32_t)tune.block * 4u;
+  out->tune = opt_tuning(hp->kind, bf16);
+  if (want_dmask) out->tune.u = SWIFT_DEFAULT_U, out->tune.block = SWIFT_DEFAULT_BLOCK;     // the only packed-table shape
+  out->kernel = pick_kernel(out->tune, hp->kind, undo, bf16, xb);
+  if (!out->kernel)
+    return fail(SWIFT_EINVAL, "launch shape U=%d BLOCK=%d is not compiled in", out->tune.u, out->tune.block);
+  const uint32_t tile_elems = (uint32_t)out->tune.u * (uint32_t)out->tune.block * 4u;
   if (want_dmask && (rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
-  std::shared_ptr<Plan> plan;
-  if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
-  if (plan->n_chunks == 0) return SWIFT_OK;
-  uint32_t tpc_shift = 0;
-  while ((tile_elems << tpc_shift) < plan->chunk_elems) ++tpc_shift;
-  const uint64_t n_slots = (uint64_t)plan->n_chunks << tpc_shift;
-  const hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const ChunkDesc *table = static_cast<const ChunkDesc *>(plan->chunks());
-  if (!want_dmask) {
-    hipLaunchKernelGGL(kernel, dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)), dim3((uint32_t)tune.block),
-                       lds_cap_bytes(info, tune), stream, table, n_slots, tpc_shift, c);
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, stream, &out->plan))) return rc;
+  if (out->plan->n_chunks == 0) return SWIFT_OK;
+  out->tpc_shift = shift_for(tile_elems, out->plan->chunk_elems);
+  out->n_slots = (uint64_t)out->plan->n_chunks << out->tpc_shift;
+  out->n_tensors = (uint32_t)l->n;
+  if (want_dmask) {
+    if ((rc = packed_prepare(*out->plan, stream))) return rc;
+    out->packed_kernel = pick_packed_kernel(hp->kind, undo, bf16, xb);
+    out->device_mask = device_mask;
+  }
+  out->empty = false;
+  return SWIFT_OK;
+}
+
+int opt_launch(const OptLaunch &L, hipStream_t stream) {
+  if (L.empty) return SWIFT_OK;
+  const Plan &plan = *L.plan;
+  const ChunkDesc *table = static_cast<const ChunkDesc *>(plan.chunks());
+  if (!L.packed_kernel) {
+    hipLaunchKernelGGL(L.kernel, dim3((uint32_t)std::min<uint64_t>(L.n_slots, 0x7fffffffull)), dim3((uint32_t)L.tune.block),
+                       lds_cap_bytes(L.info, L.tune), stream, table, L.n_slots, L.tpc_shift, L.c);
     SWIFT_HIP(hipGetLastError());
     return SWIFT_OK;
   }
@@ -587,21 +755,29 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
   // leaves the slot count beside it; the update kernel then runs over the packed table with a
   // capped grid, strides, and stops at that count: every pass of its loop has a tile to process,
   // and an almost empty mask costs at most the capped grid's idle dispatches.
-  if ((rc = packed_prepare(*plan))) return rc;
-  char *pm = static_cast<char *>(plan->packed_mem);
-  ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(pm + plan->packed_table_off);
-  uint64_t *count = reinterpret_cast<uint64_t *>(pm + plan->packed_count_off);
+  char *pm = static_cast<char *>(plan.packed_mem);
+  ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(pm + plan.packed_table_off);
+  uint64_t *count = reinterpret_cast<uint64_t *>(pm + plan.packed_count_off);
   uint64_t grid_cap = 0x7fffffffull;
-  const long per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
-  if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
-  hipLaunchKernelGGL(compact_chunks_kernel, dim3((uint32_t)l->n), dim3(kThreads), 0, stream, table,
-                     reinterpret_cast<const TensorChunks *>(pm), (uint32_t)l->n, device_mask, tpc_shift, packed, count);
+  const long per_cu = knobs().dmask_wgs_per_cu;
+  if (per_cu > 0) grid_cap = (uint64_t)L.info.cus * (uint64_t)per_cu;
+  hipLaunchKernelGGL(compact_chunks_kernel, dim3(L.n_tensors), dim3(kThreads), 0, stream, table,
+                     reinterpret_cast<const TensorChunks *>(pm), L.n_tensors, L.device_mask, L.tpc_shift, packed, count);
   SWIFT_HIP(hipGetLastError());
-  hipLaunchKernelGGL(pick_packed_kernel(hp->kind, undo, bf16, xb), dim3((uint32_t)std::min<uint64_t>(n_slots, grid_cap)),
-                     dim3((uint32_t)tune.block), lds_cap_bytes(info, tune), stream, static_cast<const ChunkDesc *>(packed),
-                     static_cast<const uint64_t *>(count), tpc_shift, c);
+  hipLaunchKernelGGL(L.packed_kernel, dim3((uint32_t)std::min<uint64_t>(L.n_slots, grid_cap)), dim3((uint32_t)L.tune.block),
+                     lds_cap_bytes(L.info, L.tune), stream, static_cast<const ChunkDesc *>(packed),
+                     static_cast<const uint64_t *>(count), L.tpc_shift, L.c);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
+}
+
+int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask,
+             const uint8_t *device_mask, bool want_dmask, bool undo, void *stream_) {
+  const hipStream_t stream = static_cast<hipStream_t>(stream_);
+  OptLaunch L;
+  int rc = opt_prepare(l, hp, host_mask, device_mask, want_dmask, undo, stream, &L);
+  if (rc) return rc;
+  return opt_launch(L, stream);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -629,9 +805,10 @@ LambApplyKernel pick_lamb_apply(int u, bool xb) {
 
 int clamp_u(long u) { return u <= 1 ? 1 : (u == 2 ? 2 : 4); }
 
-int lamb_prepare(Plan &plan, uint32_t tile_elems) {
+int lamb_prepare(Plan &plan, uint32_t tile_elems, hipStream_t stream) {
   std::lock_guard<std::mutex> lock(plan.lamb_mu);
   if (plan.lamb_spans && plan.lamb_tile_elems == tile_elems) return SWIFT_OK;
+  if (int rc = refuse_under_capture(stream, "this tensor list has not been stepped with LAMB before")) return rc;
   if (plan.lamb_spans) {               // the pass-1 tile was changed (a sweep): rebuild the scratch
     (void)hipFree(plan.lamb_spans);    // (hipFree waits for kernels that may still read it)
     (void)hipFree(plan.lamb_partial);
@@ -656,13 +833,9 @@ int lamb_prepare(Plan &plan, uint32_t tile_elems) {
   plan.lamb_partial = dpartial;
   plan.lamb_tile_elems = tile_elems;
   plan.lamb_spans = dspans;
+  plan.dev_bytes += std::max<size_t>(spans.size(), 1) * sizeof(TensorSpan) +
+                    std::max<uint64_t>((uint64_t)plan.n_chunks * tpc, 1) * sizeof(double2);
   return SWIFT_OK;
-}
-
-uint32_t shift_for(uint32_t tile_elems, uint32_t chunk_elems) {
-  uint32_t s = 0;
-  while ((tile_elems << s) < chunk_elems) ++s;
-  return s;
 }
 
 int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, double *norms,
@@ -682,16 +855,17 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
   if ((rc = check_device_range(norms, (size_t)l->n * 16, dev, "norms_device", 0))) return rc;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16, xb = l->param_bf16 != nullptr;
   std::shared_ptr<Plan> plan;
-  if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const int u1 = clamp_u(env_long("SWIFT_LAMB_U1", SWIFT_LAMB_U1)), u3 = clamp_u(env_long("SWIFT_LAMB_U3", SWIFT_LAMB_U3));
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, stream, &plan))) return rc;
+  const Knobs kn = knobs();
+  const int u1 = clamp_u(kn.lamb_u1), u3 = clamp_u(kn.lamb_u3);
   const uint32_t tile1 = (uint32_t)u1 * 256u, tile3 = (uint32_t)u3 * 256u, tileu = 256u;
   const uint32_t s1 = shift_for(tile1, plan->chunk_elems), s3 = shift_for(tile3, plan->chunk_elems);
   const uint32_t su = shift_for(tileu, plan->chunk_elems);
   const uint64_t slots1 = (uint64_t)plan->n_chunks << s1, slots3 = (uint64_t)plan->n_chunks << s3;
   const uint64_t slotsu = (uint64_t)plan->n_chunks << su;
-  const Tuning t1{u1, 64, (int)env_long("SWIFT_LAMB_WAVES_P1", SWIFT_LAMB_WAVES_P1)};
-  const Tuning t3{u3, 64, (int)env_long("SWIFT_LAMB_WAVES_P3", SWIFT_LAMB_WAVES_P3)};
+  const Tuning t1{u1, 64, (int)kn.lamb_waves_p1};
+  const Tuning t3{u3, 64, (int)kn.lamb_waves_p3};
   const Tuning tu = opt_tuning(SWIFT_ADAMW, bf16);
   const ChunkDesc *chunks = static_cast<const ChunkDesc *>(plan->chunks());
   if (undo) {
@@ -703,7 +877,7 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
     SWIFT_HIP(hipGetLastError());
     return SWIFT_OK;
   }
-  if ((rc = lamb_prepare(*plan, tile1))) return rc;
+  if ((rc = lamb_prepare(*plan, tile1, stream))) return rc;
   if (plan->n_chunks) {
     hipLaunchKernelGGL(pick_lamb_moments(u1, bf16), dim3((uint32_t)std::min<uint64_t>(slots1, 0x7fffffffull)), dim3(64),
                        lds_cap_bytes(info, t1), stream, chunks, slots1, s1, c, static_cast<double2 *>(plan->lamb_partial));
@@ -722,9 +896,18 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
 
 // ------------------------------------------------------------------------------------------
 // Optimizer step / undo fused with the digest of the new state.
-int fused_prepare(Plan &plan) {
+int fused_prepare(Plan &plan, uint32_t tile_elems, hipStream_t stream) {
   std::lock_guard<std::mutex> lock(plan.lamb_mu);
-  if (plan.fused_spans) return SWIFT_OK;
+  if (plan.fused_spans && plan.fused_tile_elems == tile_elems) return SWIFT_OK;
+  if (int rc = refuse_under_capture(stream, "this tensor list has not been used with the fused digest before")) return rc;
+  const uint64_t tile_slots = (uint64_t)std::max<uint32_t>(plan.n_chunks, 1) * (plan.chunk_elems / tile_elems);
+  if (plan.fused_spans) {              // the tile was changed (a sweep): only the tile sums change size
+    (void)hipFree(plan.fused_tiles);   // (hipFree waits for kernels that may still use it)
+    plan.fused_tiles = nullptr;
+    SWIFT_HIP(hipMalloc(&plan.fused_tiles, tile_slots * 3 * sizeof(uint64_t)));
+    plan.fused_tile_elems = tile_elems;
+    return SWIFT_OK;
+  }
   std::vector<TensorSpan> spans(plan.t_numel.size());
   for (size_t i = 0; i < spans.size(); ++i) {
     spans[i].first_slot = plan.t_first_chunk[i];
@@ -732,23 +915,30 @@ int fused_prepare(Plan &plan) {
     spans[i].active = plan.t_active[i];
     spans[i].pad = 0;
   }
-  void *dspans = nullptr, *dslots = nullptr;
+  void *dspans = nullptr, *dslots = nullptr, *dtiles = nullptr;
   SWIFT_HIP(hipMalloc(&dspans, std::max<size_t>(spans.size(), 1) * sizeof(TensorSpan)));
   hipError_t e = hipMemcpy(dspans, spans.data(), spans.size() * sizeof(TensorSpan), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMalloc(&dslots, std::max<size_t>(plan.n_chunks, 1) * 3 * sizeof(uint64_t));
+  if (e == hipSuccess) e = hipMalloc(&dtiles, tile_slots * 3 * sizeof(uint64_t));
   if (e != hipSuccess) {
     (void)hipFree(dspans);
+    if (dslots) (void)hipFree(dslots);
     return fail(SWIFT_EHIP, "digest scratch allocation failed: %s", hipGetErrorName(e));
   }
   plan.fused_slots = dslots;
+  plan.fused_tiles = dtiles;
+  plan.fused_tile_elems = tile_elems;
   plan.fused_spans = dspans;
+  plan.dev_bytes += std::max<size_t>(spans.size(), 1) * sizeof(TensorSpan) +
+                    (std::max<size_t>(plan.n_chunks, 1) + tile_slots) * 3 * sizeof(uint64_t);
   return SWIFT_OK;
 }
 
-typedef void (*FusedKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts, unsigned long long *);
+typedef void (*FusedKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts, uint64_t *);
 
-FusedKernel pick_fused(int kind, bool undo, bool bf16, bool xb) {
-#define SWIFT_PICK2(K, UNDO_, BF_) (xb ? opt_digest_kernel<K, UNDO_, BF_, true, 1, 64> : opt_digest_kernel<K, UNDO_, BF_, false, 1, 64>)
+template <int U>
+FusedKernel pick_fused_u(int kind, bool undo, bool bf16, bool xb) {
+#define SWIFT_PICK2(K, UNDO_, BF_) (xb ? opt_digest_kernel<K, UNDO_, BF_, true, U, 64> : opt_digest_kernel<K, UNDO_, BF_, false, U, 64>)
 #define SWIFT_PICK(K)                                                         \
   (undo ? (bf16 ? SWIFT_PICK2(K, true, true) : SWIFT_PICK2(K, true, false))   \
         : (bf16 ? SWIFT_PICK2(K, false, true) : SWIFT_PICK2(K, false, false)))
@@ -759,6 +949,17 @@ FusedKernel pick_fused(int kind, bool undo, bool bf16, bool xb) {
   }
 #undef SWIFT_PICK
 #undef SWIFT_PICK2
+}
+
+// Vectors per lane of the fused kernel: the default, plus the alternatives of a sweep build.
+FusedKernel pick_fused(int u, int kind, bool undo, bool bf16, bool xb) {
+#ifdef SWIFT_SWEEP_SHAPES
+  if (u == 1) return pick_fused_u<1>(kind, undo, bf16, xb);
+  if (u == 2) return pick_fused_u<2>(kind, undo, bf16, xb);
+  if (u == 4) return pick_fused_u<4>(kind, undo, bf16, xb);
+#endif
+  if (u == SWIFT_FUSED_U) return pick_fused_u<SWIFT_FUSED_U>(kind, undo, bf16, xb);
+  return nullptr;
 }
 
 int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, uint64_t *digests,
@@ -782,29 +983,32 @@ int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_
   if ((rc = check_device_range(digests, (size_t)l->n * n_groups * 8, dev, "digests_device", 0))) return rc;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16;
   std::shared_ptr<Plan> plan;
-  if ((rc = build_opt_plan(l, hp, host_mask, dev, &plan))) return rc;
-  if ((rc = fused_prepare(*plan))) return rc;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if ((rc = build_opt_plan(l, hp, host_mask, dev, stream, &plan))) return rc;
   Tuning tune = opt_tuning(hp->kind, bf16);
-  tune.u = 1;
+  tune.u = (int)knobs().fused_u;
   tune.block = 64;
   // the digest arithmetic makes this kernel ALU-heavy: more resident wavefronts overlap it with memory
-  tune.waves_per_cu = (int)env_long("SWIFT_FUSED_WAVES_PER_CU", SWIFT_FUSED_WAVES_PER_CU);
-  unsigned long long *slots = static_cast<unsigned long long *>(plan->fused_slots);
+  tune.waves_per_cu = (int)knobs().fused_waves_per_cu;
+  const FusedKernel fused_kernel = pick_fused(tune.u, hp->kind, undo, bf16, l->param_bf16 != nullptr);
+  if (!fused_kernel) return fail(SWIFT_EINVAL, "fused launch shape U=%d is not compiled in", tune.u);
+  const uint32_t tile_elems = 256u * (uint32_t)tune.u;
+  if ((rc = fused_prepare(*plan, tile_elems, stream))) return rc;
+  uint64_t *slots = static_cast<uint64_t *>(plan->fused_slots), *tiles = static_cast<uint64_t *>(plan->fused_tiles);
   if (plan->n_chunks) {
-    const uint64_t n_fill = (uint64_t)plan->n_chunks * 3;
-    hipLaunchKernelGGL(fill_u64_kernel, dim3((uint32_t)std::min<uint64_t>((n_fill + kThreads - 1) / kThreads, 4096)),
-                       dim3(kThreads), 0, stream, reinterpret_cast<uint64_t *>(slots), n_fill, (uint64_t)0);
-    SWIFT_HIP(hipGetLastError());
-    const uint32_t shift = shift_for(256u, plan->chunk_elems);
+    const uint32_t shift = shift_for(tile_elems, plan->chunk_elems);
     const uint64_t n_slots = (uint64_t)plan->n_chunks << shift;
-    hipLaunchKernelGGL(pick_fused(hp->kind, undo, bf16, l->param_bf16 != nullptr), dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)),
-                       dim3(64), lds_cap_bytes(info, tune), stream, static_cast<const ChunkDesc *>(plan->chunks()),
-                       n_slots, shift, c, slots);
+    const ChunkDesc *table = static_cast<const ChunkDesc *>(plan->chunks());
+    hipLaunchKernelGGL(fused_kernel, dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)),
+                       dim3(64), lds_cap_bytes(info, tune), stream, table, n_slots, shift, c, tiles);
+    SWIFT_HIP(hipGetLastError());
+    hipLaunchKernelGGL(chunk_digest_kernel, dim3(plan->n_chunks), dim3(kThreads), 0, stream, table, shift, tile_elems,
+                       n_groups, static_cast<const uint64_t *>(tiles), slots);
     SWIFT_HIP(hipGetLastError());
   }
   hipLaunchKernelGGL(digest_gather_kernel, dim3((uint32_t)l->n), dim3(64), 0, stream,
-                     static_cast<const TensorSpan *>(plan->fused_spans), slots, (uint32_t)l->n, n_groups, digests);
+                     static_cast<const TensorSpan *>(plan->fused_spans), static_cast<const uint64_t *>(slots), (uint32_t)l->n,
+                     n_groups, digests);
   SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }
@@ -834,8 +1038,8 @@ int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, b
 // one address (whole-tensor shards of large tensors), but the launch still needs about sixteen
 // workgroups per compute unit to fill the chip, so the length follows the total size.
 uint32_t digest_chunk_elems(uint64_t total, int64_t shard_elems, int cus) {
-  const uint32_t tile = 4u * kThreads * 4;                     // largest unroll the kernel is built with
-  long forced = env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0);       // tuning knob for sweeps
+  const uint32_t tile = 4u * kThreads * 4;                     // chunk lengths are multiples of four rounds of the kernel
+  const long forced = knobs().digest_chunk_elems;              // tuning knob for sweeps
   if (forced >= (long)tile && forced <= (1l << 22) && forced % tile == 0) return (uint32_t)forced;
   const uint32_t cap = shard_elems == 0 ? 4u * SWIFT_DIGEST_CHUNK : SWIFT_DIGEST_CHUNK;
   const uint64_t want = total / (16ull * (uint64_t)cus);
@@ -845,21 +1049,30 @@ uint32_t digest_chunk_elems(uint64_t total, int64_t shard_elems, int cus) {
 }
 
 int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *numel, int64_t shard_elems, int dev,
-                      int cus, std::shared_ptr<Plan> *out) {
+                      int cus, hipStream_t stream, std::shared_ptr<Plan> *out) {
   std::string key;
   key.reserve(64 + (size_t)n_buf * 16);
   key_add(key, (uint8_t)'D');
   key_add(key, dev);
   key_add(key, n_buf);
   key_add(key, shard_elems);
-  key_add(key, env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0));
+  key_add(key, knobs().digest_chunk_elems);
   for (int64_t i = 0; i < n_buf; ++i) {
     key_add(key, numel[i]);
     key_add(key, buf[i]);
   }
   if (auto hit = find_plan(key)) {
-    *out = hit;
-    return SWIFT_OK;
+    bool stale = false;
+    int rc = reuse_plan(hit, stream, &stale);
+    if (rc) return rc;
+    if (!stale) {
+      *out = hit;
+      return SWIFT_OK;
+    }
+  }
+  {
+    int rc = refuse_under_capture(stream, "this buffer list has not been digested before");
+    if (rc) return rc;
   }
   std::vector<DigestDesc> descs((size_t)n_buf);
   uint64_t total = 0, n_out = 0;
@@ -899,6 +1112,8 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   int rc = upload_plan(*plan, descs.data(), descs.size() * sizeof(DigestDesc), chunks.data(), chunks.size(),
                        sizeof(ChunkRef));
   if (rc) return rc;
+  for (int64_t i = 0; i < n_buf && !plan->probe_ptr; ++i)
+    if (numel[i] > 0) set_probe(*plan, buf[i]);
   keep_plan(plan);
   *out = plan;
   return SWIFT_OK;
@@ -992,11 +1207,9 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
     DeviceInfo info;
     if ((rc = device_info(dev, &info))) return rc;
     if ((rc = check_device_range(out_device, (size_t)n_out * 8, dev, "out_device", 0))) return rc;
-    const long du = env_long("SWIFT_DIGEST_U", SWIFT_DIGEST_U);   // tuning knob for sweeps
-    const auto kernel = du == 1 ? digest_kernel<1> : du == 2 ? digest_kernel<2> : digest_kernel<4>;
     std::shared_ptr<Plan> plan;
-    if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, info.cus, &plan))) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, info.cus, stream, &plan))) return rc;
     // The output is cleared by a kernel (not a memset node) so that the call can be captured in a graph.
     const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
     hipLaunchKernelGGL(fill_u64_kernel, dim3(fill_grid), dim3(kThreads), 0, stream, out_device, (uint64_t)n_out,
@@ -1004,7 +1217,7 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
     SWIFT_HIP(hipGetLastError());
     if (plan->n_chunks == 0) return SWIFT_OK;
     const uint32_t grid = plan->n_chunks;                        // one workgroup per chunk
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
+    hipLaunchKernelGGL(digest_kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
                        static_cast<const ChunkRef *>(plan->chunks()), plan->n_chunks, plan->chunk_elems,
                        (uint64_t)shard_elems,
                        reinterpret_cast<unsigned long long *>(out_device));
@@ -1054,8 +1267,8 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
     // A copy moves only 2 x 16 bytes per lane, so unlike the update kernels it wants every wavefront slot of
     // a CU filled: one vector per lane and no residency cap measured best (6.7 TB/s; 4.3 with the update
     // kernels' cap of 11).  Knobs for sweeps.
-    const int u = clamp_u(env_long("SWIFT_COPY_U", SWIFT_COPY_U));
-    const Tuning tune{u, SWIFT_DEFAULT_BLOCK, (int)env_long("SWIFT_COPY_WAVES_PER_CU", SWIFT_COPY_WAVES_PER_CU)};
+    const int u = clamp_u(knobs().copy_u);
+    const Tuning tune{u, SWIFT_DEFAULT_BLOCK, (int)knobs().copy_waves_per_cu};
     const uint64_t n16 = (uint64_t)bytes / 16;
     const uint64_t tile = (uint64_t)u * SWIFT_DEFAULT_BLOCK;
     const uint64_t tiles = (n16 + tile - 1) / tile;
@@ -1162,6 +1375,9 @@ int swift_tracker_step(swift_tracker *tr, const swift_tensor_list *group, const 
     if (t.device < 0) t.device = dev;
     if (dev != t.device) return fail(SWIFT_EINVAL, "tracker: created for device %d, current device is %d", t.device, dev);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // everything that can be refused is checked before anything is enqueued, the stream wait included
+    OptLaunch launch;
+    if (int rc = opt_prepare(group, hp, nullptr, nullptr, false, false, stream, &launch)) return rc;
     hipEvent_t done;
     if (!t.pool.empty()) {
       done = t.pool.back();
@@ -1178,10 +1394,10 @@ int swift_tracker_step(swift_tracker *tr, const swift_tensor_list *group, const 
         return fail(SWIFT_EHIP, "hipStreamWaitEvent failed: %s", hipGetErrorName(e));
       }
     }
-    const int rc = swift_opt_step(group, hp, nullptr, hip_stream);
+    const int rc = opt_launch(launch, stream);
     if (rc != SWIFT_OK) {
       t.pool.push_back(done);
-      return rc;                         // nothing was launched, nothing is marked
+      return rc;                         // the launch itself failed (SWIFT_EHIP): nothing is marked
     }
     hipError_t e = hipEventRecord(done, stream);
     if (e != hipSuccess) {
@@ -1202,7 +1418,7 @@ int swift_tracker_marks(swift_tracker *tr, uint8_t *host_mask_out) {
   if (!host_mask_out && tr->t.n_tensors > 0) return fail(SWIFT_EINVAL, "tracker: host_mask_out is NULL");
   Tracker &t = tr->t;
   std::lock_guard<std::mutex> lock(t.mu);
-  int rc = tracker_wait(t);            // "we need to let these kernels finish executing"
+  int rc = tracker_wait(t);            // launched update kernels run to completion before the marks are read (Implementation, "Update-undo")
   if (rc) return rc;
   if (t.n_tensors) memcpy(host_mask_out, t.marks.data(), (size_t)t.n_tensors);
   return SWIFT_OK;
@@ -1252,6 +1468,44 @@ int swift_logging_groups(int64_t n_machines, const double *compute_time, const d
     if (recovery_out) *recovery_out = r.recovery;
     return SWIFT_OK;
   });
+}
+
+int swift_cache_stats(int64_t *n_lists, int64_t *device_bytes) {
+  int64_t n = 0, bytes = 0;
+  {
+    std::lock_guard<std::mutex> lock(g_plan_mu);
+    if (g_plans)
+      for (const auto &p : g_plans->lru) {
+        ++n;
+        bytes += (int64_t)p->dev_bytes;
+      }
+  }
+  if (n_lists) *n_lists = n;
+  if (device_bytes) *device_bytes = bytes;
+  return SWIFT_OK;
+}
+
+int swift_cache_trim(int64_t max_device_bytes) {
+  if (max_device_bytes < 0) return fail(SWIFT_EINVAL, "cache_trim: max_device_bytes must be >= 0");
+  std::list<std::shared_ptr<Plan>> drop;
+  {
+    std::lock_guard<std::mutex> lock(g_plan_mu);
+    if (g_plans) {
+      int64_t bytes = 0;
+      for (const auto &p : g_plans->lru) bytes += (int64_t)p->dev_bytes;
+      // least recently used first; plans that a captured graph may replay stay
+      for (auto it = g_plans->lru.end(); bytes > max_device_bytes && it != g_plans->lru.begin();) {
+        --it;
+        if ((*it)->pinned) continue;
+        bytes -= (int64_t)(*it)->dev_bytes;
+        g_plans->index.erase((*it)->key);
+        drop.push_back(*it);
+        it = g_plans->lru.erase(it);
+      }
+    }
+  }
+  drop.clear();   // ~Plan frees (and thereby synchronises) on each plan's device
+  return SWIFT_OK;
 }
 
 int swift_shutdown(void) {

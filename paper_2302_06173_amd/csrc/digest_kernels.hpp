@@ -23,15 +23,32 @@ constexpr uint64_t kK2 = 0x6A09E667F3BCC909ull;
 constexpr uint64_t kK3 = 0xBB67AE8584CAA73Bull;
 
 // z = (i << 32) | w;  z += K1;  z ^= z >> 32;  z *= K2;  z ^= z >> 29;  z *= K3;  z ^= z >> 32
-__device__ __forceinline__ uint64_t digest_mix(uint32_t i, uint32_t w) {
-  uint64_t z = ((uint64_t)i << 32) | (uint64_t)w;
-  z += kK1;
-  z ^= z >> 32;
+// The first two steps are written on the 32-bit halves: the low half is w + K1.lo, the high half
+// i + K1.hi + carry (one add-with-carry pair, and when i is a register plus a constant the constant
+// folds into K1.hi), and after z ^= z >> 32 the low half is lo ^ hi.  Every instruction of the mixer
+// issues at full rate on gfx950 (32-bit multiplies and 64-bit shifts included); 16 per word is the
+// floor: a 64 x 64 -> 64 bit multiply takes two 32-bit multiplies, one 32 x 32 -> 64 and a 3-input add.
+// digest_mix_pre takes i + K1.hi (mod 2^32), which a loop over consecutive words keeps in a register.
+__device__ __forceinline__ uint64_t digest_mix_pre(uint32_t i_plus_k1hi, uint32_t w) {
+  uint32_t lo;
+  const uint32_t carry = __builtin_uadd_overflow(w, (uint32_t)kK1, &lo) ? 1u : 0u;
+  const uint32_t hi = i_plus_k1hi + carry;
+  uint64_t z = ((uint64_t)hi << 32) | (uint64_t)(lo ^ hi);
   z *= kK2;
   z ^= z >> 29;
   z *= kK3;
   z ^= z >> 32;
   return z;
+}
+
+__device__ __forceinline__ uint64_t digest_mix(uint32_t i, uint32_t w) {
+  return digest_mix_pre(i + (uint32_t)(kK1 >> 32), w);
+}
+
+// The four words of one 16-byte vector whose first word has index e: pass e + K1.hi.
+__device__ __forceinline__ uint64_t digest_mix4_pre(uint32_t e_plus_k1hi, const u32x4 &r) {
+  return (digest_mix_pre(e_plus_k1hi, r[0]) + digest_mix_pre(e_plus_k1hi + 1u, r[1])) +
+         (digest_mix_pre(e_plus_k1hi + 2u, r[2]) + digest_mix_pre(e_plus_k1hi + 3u, r[3]));
 }
 
 // Lane exchange inside a row of 16 lanes through the DPP data path.
@@ -42,12 +59,18 @@ __device__ __forceinline__ uint64_t dpp_fetch_u64(uint64_t s) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-// Sum of `s` over the 64 lanes of the wavefront (mod 2^64); the result is wave-uniform.
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t s) {
+// Sum of `s` over each row of 16 lanes (mod 2^64): afterwards every lane holds its row's sum.
+__device__ __forceinline__ uint64_t row_sum_u64(uint64_t s) {
   s += dpp_fetch_u64<0xB1>(s);    // quad_perm [1,0,3,2]: lane ^ 1
   s += dpp_fetch_u64<0x4E>(s);    // quad_perm [2,3,0,1]: lane ^ 2   -> every lane holds its quad's sum
   s += dpp_fetch_u64<0x141>(s);   // row_half_mirror: lane i <-> 7-i   -> sum of 8
   s += dpp_fetch_u64<0x140>(s);   // row_mirror:      lane i <-> 15-i  -> sum of the row of 16
+  return s;
+}
+
+// Sum of `s` over the 64 lanes of the wavefront (mod 2^64); the result is wave-uniform.
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t s) {
+  s = row_sum_u64(s);
   uint64_t total = 0;
 #pragma unroll
   for (int row = 0; row < 4; ++row) {
@@ -68,7 +91,6 @@ __global__ void __launch_bounds__(kThreads) fill_u64_kernel(uint64_t *p, uint64_
 // chunk = shard * cps + k covers words [shard*S + k*CE, ...) of the buffer, i.e. shard-relative
 // indices [k*CE, min(k*CE + CE, shard length)).  S = shard_elems, or numel when shard_elems = 0.
 // `out` must be zero when the kernel starts.
-template <int U>
 __global__ void __launch_bounds__(kThreads)
 digest_kernel(const DigestDesc *__restrict__ descs, const ChunkRef *__restrict__ chunks, uint32_t n_chunks,
               uint32_t chunk_elems, uint64_t shard_elems, unsigned long long *__restrict__ out) {
@@ -100,24 +122,14 @@ digest_kernel(const DigestDesc *__restrict__ descs, const ChunkRef *__restrict__
 
     uint64_t acc = 0;
     if (tid < head) acc += digest_mix(idx0 + tid, ld<false>(p + tid));
+    // One 16-byte load per lane and round, mixed as soon as it arrives.  The kernel is bound by
+    // instruction issue (about 16 vector instructions per word, at a shader clock the chip lowers
+    // under this load), not by load latency: issuing the next round's load ahead of the mixing
+    // (software pipelining) and several loads per lane were measured and are slower.
+    uint32_t ek = ib + (tid << 2) + (uint32_t)(kK1 >> 32);       // index of this lane's next vector, + K1.hi
     uint32_t i = 0;
-    for (; i + U * kThreads <= n4; i += U * kThreads) {
-      u32x4 r[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) r[u] = ld<NT>(p4 + i + u * kThreads + tid);
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const uint32_t e = ib + ((i + u * kThreads + tid) << 2);
-        acc += digest_mix(e, r[u][0]) + digest_mix(e + 1, r[u][1]);
-        acc += digest_mix(e + 2, r[u][2]) + digest_mix(e + 3, r[u][3]);
-      }
-    }
-    for (uint32_t j = i + tid; j < n4; j += kThreads) {
-      const u32x4 r = ld<NT>(p4 + j);
-      const uint32_t e = ib + (j << 2);
-      acc += digest_mix(e, r[0]) + digest_mix(e + 1, r[1]);
-      acc += digest_mix(e + 2, r[2]) + digest_mix(e + 3, r[3]);
-    }
+    for (; i + kThreads <= n4; i += kThreads, ek += kThreads * 4u) acc += digest_mix4_pre(ek, ld<NT>(p4 + i + tid));   // full rounds: no predicate
+    if (i + tid < n4) acc += digest_mix4_pre(ek, ld<NT>(p4 + i + tid));
     if (tail0 + tid < len) acc += digest_mix(idx0 + tail0 + tid, ld<false>(p + tail0 + tid));
 
     const uint64_t wsum = wave_sum_u64(acc);

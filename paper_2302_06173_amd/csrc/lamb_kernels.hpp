@@ -54,7 +54,7 @@ struct LambMomentsOp {
     const double x = (double)xf, g = (double)gf;
     const double mt = fma(c.b1, (double)mf, c.c1 * g);
     const double vt = fma(c.b2, (double)vf, c.c2 * (g * g));
-    const double r = (mt * c.rbc1) / (sqrt(vt * c.rbc2) + c.eps);
+    const double r = (mt * c.rbc1) / (sqrt_moment(vt * c.rbc2) + c.eps);
     const double u = fma(c.lam, x, r);
     mf = (float)mt;
     vf = (float)vt;
@@ -71,7 +71,7 @@ struct LambApplyOp {
   double eta_q;
   __device__ __forceinline__ void elem(uint32_t, float &xf, float, float &mf, float &vf) {
     const double x = (double)xf;
-    const double r = ((double)mf * c.rbc1) / (sqrt((double)vf * c.rbc2) + c.eps);
+    const double r = ((double)mf * c.rbc1) / (sqrt_moment((double)vf * c.rbc2) + c.eps);
     xf = (float)fma(-eta_q, fma(c.lam, x, r), x);
   }
 };

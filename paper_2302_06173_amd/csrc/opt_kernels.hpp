@@ -16,25 +16,58 @@ namespace swift {
 constexpr int kSGDM = 0, kADAM = 1, kADAMW = 2;
 constexpr int kThreads = 256;           // 4 wavefronts of 64
 // Launch shapes of the optimizer kernels that get compiled: X(U, BLOCK) = 16-byte vectors per lane,
-// lanes per workgroup.  The default is the measured best; the others serve sweeps.
+// lanes per workgroup.  The product builds the measured best only; -DSWIFT_SWEEP_SHAPES adds the
+// shapes that sweeps compare it with (SWIFT_TILE_U / SWIFT_TILE_BLOCK select among them).
 #ifndef SWIFT_SHAPES
+#ifdef SWIFT_SWEEP_SHAPES
 #define SWIFT_SHAPES(X) X(1, 64) X(2, 64) X(4, 64) X(1, 256)
+#else
+#define SWIFT_SHAPES(X) X(1, 64)
+#endif
 #endif
 // Tuning defaults, all measured on MI355X with the 7 B-parameter list (wavefronts per compute unit
-// are enforced through unused dynamic LDS).
-#ifndef SWIFT_DEFAULT_U
-#define SWIFT_DIGEST_U 1                // digest kernel: 16-byte loads in flight per lane
+// are enforced through unused dynamic LDS).  Each can be overridden on the compiler's command line.
+#ifndef SWIFT_DIGEST_CHUNK
 #define SWIFT_DIGEST_CHUNK 65536        // digest kernel: words per workgroup (large inputs)
+#endif
+#ifndef SWIFT_DEFAULT_U
 #define SWIFT_DEFAULT_U 1
+#endif
+#ifndef SWIFT_DEFAULT_BLOCK
 #define SWIFT_DEFAULT_BLOCK 64
+#endif
+#ifndef SWIFT_DEFAULT_WAVES_PER_CU
 #define SWIFT_DEFAULT_WAVES_PER_CU 11
+#endif
+#ifndef SWIFT_DEFAULT_WAVES_PER_CU_SGDM
 #define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
+#endif
+#ifndef SWIFT_FUSED_U
+#define SWIFT_FUSED_U 1                 // step/undo fused with the digest: vectors per lane
+#endif
+#ifndef SWIFT_FUSED_WAVES_PER_CU
 #define SWIFT_FUSED_WAVES_PER_CU 24     // step/undo fused with the digest
+#endif
+#ifndef SWIFT_LAMB_U1
 #define SWIFT_LAMB_U1 4                 // LAMB pass 1: vectors per lane (tile = U * 256 elements)
+#endif
+#ifndef SWIFT_LAMB_U3
 #define SWIFT_LAMB_U3 1                 // LAMB pass 3
+#endif
+#ifndef SWIFT_LAMB_WAVES_P1
 #define SWIFT_LAMB_WAVES_P1 6           // LAMB pass 1 (U = 4): wavefronts per CU
+#endif
+#ifndef SWIFT_LAMB_WAVES_P3
 #define SWIFT_LAMB_WAVES_P3 24          // LAMB pass 3 (3 streams in, 1 out)
+#endif
+#ifndef SWIFT_DEFAULT_DMASK_WGS_PER_CU
 #define SWIFT_DEFAULT_DMASK_WGS_PER_CU 16384
+#endif
+#ifndef SWIFT_COPY_U
+#define SWIFT_COPY_U 1                  // copy kernel: 16-byte vectors per lane
+#endif
+#ifndef SWIFT_COPY_WAVES_PER_CU
+#define SWIFT_COPY_WAVES_PER_CU 0       // copy kernel: residency cap (0 = none: measured best, 6.7 TB/s)
 #endif
 #ifndef SWIFT_NT
 #define SWIFT_NT 1                      // non-temporal (streaming) loads and stores
@@ -96,12 +129,6 @@ __device__ __forceinline__ void st(T *p, T val) {
 // for the 4-read/3-write stream: loads `nt`; stores `sc0 sc1 nt` (2-3 % above `nt` alone,
 // 9 % above default stores).
 #ifndef SWIFT_LOAD_AUX
-#ifndef SWIFT_COPY_U
-#define SWIFT_COPY_U 1                      // copy kernel: 16-byte vectors per lane
-#endif
-#ifndef SWIFT_COPY_WAVES_PER_CU
-#define SWIFT_COPY_WAVES_PER_CU 0           // copy kernel: residency cap (0 = none: measured best, 6.7 TB/s)
-#endif
 #define SWIFT_LOAD_AUX 2                // nt
 #endif
 #ifndef SWIFT_STORE_AUX
@@ -125,6 +152,25 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   const uint32_t u = __float_as_uint(f);
   if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Square root of a binary64 that is at least 2^-767 or zero, negative, infinite or NaN -- which holds
+// for every second moment here: a binary32 value, or beta2 * binary32 + (1-beta2) * (binary32)^2, times
+// 1/(1-beta2^t) >= 1.  It is the compiler's own binary64 expansion (reciprocal-root seed, two coupled
+// Newton steps, two residual corrections; 0 and +inf pass through, negative gives NaN) without the
+// rescaling of arguments below 2^-767 that cannot occur here: same result bits, five instructions fewer.
+__device__ __forceinline__ double sqrt_moment(double x) {
+  const double y = __builtin_amdgcn_rsq(x);
+  double g = x * y;
+  double h = y * 0.5;
+  const double r = fma(-h, g, 0.5);
+  g = fma(g, r, g);
+  h = fma(h, r, h);
+  double d = fma(-g, g, x);
+  g = fma(d, h, g);
+  d = fma(-g, g, x);
+  g = fma(d, h, g);
+  return __builtin_amdgcn_class(x, 0x260) ? x : g;                 // +-0 and +inf: the argument itself
 }
 
 // One element.  The vector body and the scalar head/tail path both call this, so an element's
@@ -153,13 +199,16 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
       const double gp = (KIND == kADAM) ? fma(c.lam, x, g) : g;
       const double mt = fma(c.b1, m, c.c1 * gp);
       const double vt = fma(c.b2, v, c.c2 * (gp * gp));
-      const double u = (mt * c.rbc1) / (sqrt(vt * c.rbc2) + c.eps);
+      // coupled decay can make g' = g + lambda x arbitrarily small in binary64 (an absurdly small lambda), so
+      // Adam's step keeps the general root; with the raw binary32 gradient the argument is in sqrt_moment's range
+      const double root = (KIND == kADAM) ? sqrt(vt * c.rbc2) : sqrt_moment(vt * c.rbc2);
+      const double u = (mt * c.rbc1) / (root + c.eps);
       mf = (float)mt;
       vf = (float)vt;
       if constexpr (KIND == kADAM) xf = (float)fma(-c.eta, u, x);
       else xf = (float)fma(-c.eta, fma(c.lam, x, u), x);
     } else {                                        // App. A "Undo Adam" / "Undo AdamW"
-      const double u = (m * c.rbc1) / (sqrt(v * c.rbc2) + c.eps);
+      const double u = (m * c.rbc1) / (sqrt_moment(v * c.rbc2) + c.eps);
       double xt = fma(c.eta, u, x);
       if constexpr (KIND == kADAMW) xt *= c.inv_oml;
       const double gp = (KIND == kADAM) ? fma(c.lam, xt, g) : g;
