@@ -166,6 +166,23 @@ int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp,
                          const uint8_t *device_mask, void *hip_stream);
 
+/* swift_opt_undo_dmask for callers that cannot allocate device memory: code under HIP graph capture
+ * whose list has no tables yet, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same result bits.  The call makes no allocation and no copy: its chunk table, packed table and
+ * counters live in a device array that is part of the library's code object (4.1 MiB per GPU, held
+ * from the first use of the library on that GPU until the process ends), and the table is written by
+ * kernels from descriptors passed in their arguments, so nothing is cached per list either.  Limits:
+ * at most SWIFT_NOALLOC_MAX_TENSORS tensors, and the list must fit SWIFT_NOALLOC_MAX_CHUNKS chunks of
+ * at most 4 Mi elements (about 137 G elements in long tensors; every tensor takes at least one chunk);
+ * beyond that, and if list->param_bf16 is given, the call returns SWIFT_EINVAL.  All calls on one GPU
+ * share the one array: two such calls that overlap in time on a GPU race, whatever their lists and
+ * streams; on one stream they are ordered.  The first library call on a GPU performs one-time set-up
+ * (code loading, symbol lookup); make it outside a capture.  Pointers are checked in full on every call. */
+#define SWIFT_NOALLOC_MAX_TENSORS 4096
+#define SWIFT_NOALLOC_MAX_CHUNKS 32768
+int swift_opt_undo_dmask_noalloc(const swift_tensor_list *list, const swift_hparams *hp,
+                                 const uint8_t *device_mask, void *hip_stream);
+
 /* swift_opt_step / swift_opt_undo that also return the digests of the state they leave behind, at no
  * extra HBM traffic: digests_device[g * n + i] is the digest of tensor i's theta (g = 0), m (g = 1) and
  * v (g = 2; SGDM has g = 0, 1 only), one shard per tensor, identical to what swift_state_digest writes

@@ -43,7 +43,8 @@ class SwiftTensorList(ctypes.Structure):
 
 
 _P = ctypes.c_void_p
-for _name in ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask"):
+for _name in ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask",
+              "swift_opt_undo_dmask_noalloc"):
     getattr(_lib, _name).argtypes = [ctypes.POINTER(SwiftTensorList), ctypes.POINTER(SwiftHparams), _P, _P]
     getattr(_lib, _name).restype = ctypes.c_int
 for _name in ("swift_lamb_step", "swift_lamb_undo", "swift_opt_step_digest", "swift_opt_undo_digest"):
@@ -77,7 +78,7 @@ _lib.swift_last_error.argtypes = []
 _lib.swift_last_error.restype = ctypes.c_char_p
 
 EXPORTS = ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask",
-           "swift_cache_stats", "swift_cache_trim",
+           "swift_opt_undo_dmask_noalloc", "swift_cache_stats", "swift_cache_trim",
            "swift_lamb_step", "swift_lamb_undo", "swift_opt_step_digest", "swift_opt_undo_digest",
            "swift_tracker_create", "swift_tracker_begin", "swift_tracker_step", "swift_tracker_marks",
            "swift_tracker_undo", "swift_tracker_destroy",
@@ -200,6 +201,11 @@ def swift_opt_step_dmask(tl: TensorList, hp: SwiftHparams, device_mask: torch.Te
 def swift_opt_undo_dmask(tl: TensorList, hp: SwiftHparams, device_mask: torch.Tensor, stream=None) -> None:
     _check(_lib.swift_opt_undo_dmask(ctypes.byref(tl.c), ctypes.byref(hp), _dmask_ptr(device_mask, tl.n),
                                      _stream_handle(stream)))
+
+
+def swift_opt_undo_dmask_noalloc(tl: TensorList, hp: SwiftHparams, device_mask: torch.Tensor, stream=None) -> None:
+    _check(_lib.swift_opt_undo_dmask_noalloc(ctypes.byref(tl.c), ctypes.byref(hp), _dmask_ptr(device_mask, tl.n),
+                                             _stream_handle(stream)))
 
 
 def _norms_ptr(norms: torch.Tensor, n: int) -> int:

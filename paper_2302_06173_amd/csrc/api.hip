@@ -781,6 +781,202 @@ int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t 
 }
 
 // ------------------------------------------------------------------------------------------
+// swift_opt_undo_dmask_noalloc: the device-mask undo for callers that cannot allocate.  Chunk table,
+// tensor spans, packed table and slot count live in one file-scope device array instead of per-list
+// allocations; the chunk table is written by a kernel from descriptors that travel in its arguments
+// (no host-to-device copy), so the call consists of kernel launches only.
+constexpr int64_t kNoallocMaxTensors = SWIFT_NOALLOC_MAX_TENSORS;
+constexpr int64_t kNoallocMaxChunks = SWIFT_NOALLOC_MAX_CHUNKS;
+constexpr size_t kNoallocTableOff = 0;
+constexpr size_t kNoallocPackedOff = kNoallocTableOff + (size_t)kNoallocMaxChunks * sizeof(ChunkDesc);
+constexpr size_t kNoallocSpansOff = kNoallocPackedOff + (size_t)kNoallocMaxChunks * sizeof(ChunkDesc);
+constexpr size_t kNoallocCountOff = kNoallocSpansOff + (size_t)kNoallocMaxTensors * sizeof(TensorChunks);
+constexpr size_t kNoallocBytes = kNoallocCountOff + 256;
+
+// Every GPU the library runs on holds its own copy of this array until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress; kernels get the address that call returned.
+static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on device `dev`, which must be the current device; looked up once per device.
+int scratch_for_device(int dev, void **out) {
+  if (dev < 0 || dev >= kMaxDevices) return fail(SWIFT_EINVAL, "device %d is beyond the %d devices this entry point serves", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    SWIFT_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(SWIFT_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SWIFT_OK;
+}
+
+// Up to kExpandBatch tensors per launch travel by value in the kernel arguments (under the 4 KiB limit).
+constexpr int kExpandBatch = 48;
+struct ExpandTensor {
+  float *x;
+  const void *g;
+  float *m;
+  float *v;
+  uint64_t numel;
+  uint32_t first_chunk;      // position of the tensor's first chunk in the table
+  uint32_t vec_ok;
+};
+struct ExpandBatch {
+  ExpandTensor t[kExpandBatch];
+  uint32_t first_tensor;     // index of t[0] in the caller's list
+  uint32_t count;
+  uint32_t chunk_elems;
+  uint32_t g_elem_bytes;     // 4 (binary32 gradients) or 2 (bfloat16)
+};
+
+// One workgroup per tensor of the batch: writes the tensor's chunk entries and its span.
+__global__ void __launch_bounds__(kThreads)
+expand_chunks_kernel(const ExpandBatch b, ChunkDesc *__restrict__ table, TensorChunks *__restrict__ spans) {
+  if (blockIdx.x >= b.count) return;
+  const ExpandTensor t = b.t[blockIdx.x];
+  const uint64_t ce = b.chunk_elems;
+  const uint32_t n_chunks = (uint32_t)((t.numel + ce - 1) / ce);
+  for (uint32_t k = threadIdx.x; k < n_chunks; k += kThreads) {
+    const uint64_t off = (uint64_t)k * ce;
+    const uint64_t left = t.numel - off;
+    ChunkDesc d;
+    d.x = t.x + off;
+    d.g = static_cast<const char *>(t.g) + off * b.g_elem_bytes;
+    d.m = t.m + off;
+    d.v = t.v ? t.v + off : nullptr;
+    d.xb = nullptr;
+    d.len = (uint32_t)(left < ce ? left : ce);
+    d.tensor = b.first_tensor + blockIdx.x;
+    d.vec_ok = t.vec_ok;
+    d.elem0 = (uint32_t)off;
+    d.pad = 0;
+    table[t.first_chunk + k] = d;
+  }
+  if (threadIdx.x == 0) spans[b.first_tensor + blockIdx.x] = TensorChunks{t.first_chunk, n_chunks};
+}
+
+// Host-side work areas of the entry point (no heap use on the call path); guarded by g_noalloc_mu.
+std::mutex g_noalloc_mu;
+Interval g_noalloc_iv[kNoallocMaxTensors * 4];
+
+int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *device_mask, void *stream_) {
+  OptConsts c;
+  int rc = validate_hparams(hp, true, &c);
+  if (rc) return rc;
+  if (hp->kind == SWIFT_LAMB) return fail(SWIFT_EINVAL, "LAMB needs the saved norms: use swift_lamb_undo");
+  if ((rc = validate_list(l, hp))) return rc;
+  if (l->n == 0) return SWIFT_OK;
+  if (l->param_bf16) return fail(SWIFT_EINVAL, "swift_opt_undo_dmask_noalloc does not take param_bf16");
+  if (!device_mask) return fail(SWIFT_EINVAL, "device mask is NULL");
+  if (l->n > kNoallocMaxTensors)
+    return fail(SWIFT_EINVAL, "swift_opt_undo_dmask_noalloc takes at most %lld tensors per call (got %lld)",
+                (long long)kNoallocMaxTensors, (long long)l->n);
+  uint64_t total = 0, longest = 0;
+  for (int64_t i = 0; i < l->n; ++i) {
+    total += (uint64_t)l->numel[i];
+    longest = std::max<uint64_t>(longest, (uint64_t)l->numel[i]);
+  }
+  // the shortest chunk length (a power of two, at least the small-list length) whose table fits
+  uint32_t ce = 16384;
+  auto chunks_at = [&](uint64_t len) {
+    uint64_t n = 0;
+    for (int64_t i = 0; i < l->n; ++i) n += ((uint64_t)l->numel[i] + len - 1) / len;
+    return n;
+  };
+  while (ce < (1u << 22) && chunks_at(ce) > (uint64_t)kNoallocMaxChunks) ce *= 2;
+  if (chunks_at(ce) > (uint64_t)kNoallocMaxChunks)
+    return fail(SWIFT_EINVAL, "swift_opt_undo_dmask_noalloc: %llu elements in %lld tensors need more than %lld chunks of "
+                "%u elements; split the list", (unsigned long long)total, (long long)l->n, (long long)kNoallocMaxChunks, ce);
+  (void)longest;
+  int dev = -1;
+  SWIFT_HIP(hipGetDevice(&dev));
+  DeviceInfo info;
+  if ((rc = device_info(dev, &info))) return rc;
+  void *base = nullptr;
+  if ((rc = scratch_for_device(dev, &base))) return rc;
+  const bool bf16 = hp->grad_dtype == SWIFT_BF16, hasv = hp->kind != SWIFT_SGDM;
+  const size_t gsz = bf16 ? 2 : 4;
+  if ((rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
+  std::lock_guard<std::mutex> lock(g_noalloc_mu);
+  size_t n_iv = 0;
+  for (int64_t i = 0; i < l->n; ++i) {
+    const uint64_t n = (uint64_t)l->numel[i];
+    if (n == 0) continue;
+    if ((rc = check_device_range(l->param[i], n * 4, dev, "param", i))) return rc;
+    if ((rc = check_device_range(l->grad[i], n * gsz, dev, "grad", i))) return rc;
+    if ((rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
+    if (hasv && (rc = check_device_range(l->v[i], n * 4, dev, "v", i))) return rc;
+    const uintptr_t x = (uintptr_t)l->param[i], g = (uintptr_t)l->grad[i], m = (uintptr_t)l->m[i];
+    g_noalloc_iv[n_iv++] = {x, x + n * 4, true};
+    g_noalloc_iv[n_iv++] = {g, g + n * gsz, false};
+    g_noalloc_iv[n_iv++] = {m, m + n * 4, true};
+    if (hasv) g_noalloc_iv[n_iv++] = {(uintptr_t)l->v[i], (uintptr_t)l->v[i] + n * 4, true};
+  }
+  if ((rc = check_no_overlap(g_noalloc_iv, n_iv))) return rc;
+
+  char *sb = static_cast<char *>(base);
+  ChunkDesc *table = reinterpret_cast<ChunkDesc *>(sb + kNoallocTableOff);
+  ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(sb + kNoallocPackedOff);
+  TensorChunks *spans = reinterpret_cast<TensorChunks *>(sb + kNoallocSpansOff);
+  uint64_t *count = reinterpret_cast<uint64_t *>(sb + kNoallocCountOff);
+  const hipStream_t stream = static_cast<hipStream_t>(stream_);
+  Tuning tune = opt_tuning(hp->kind, bf16);
+  tune.u = SWIFT_DEFAULT_U, tune.block = SWIFT_DEFAULT_BLOCK;
+  const uint32_t tile_elems = (uint32_t)tune.u * (uint32_t)tune.block * 4u;
+  const uint32_t tpc_shift = shift_for(tile_elems, ce);
+
+  // 1. the chunk table and the spans, written on the device from by-value descriptors
+  ExpandBatch batch;
+  uint32_t next_chunk = 0;
+  for (int64_t i0 = 0; i0 < l->n; i0 += kExpandBatch) {
+    const int64_t cnt = std::min<int64_t>(kExpandBatch, l->n - i0);
+    memset(&batch, 0, sizeof batch);
+    batch.first_tensor = (uint32_t)i0;
+    batch.count = (uint32_t)cnt;
+    batch.chunk_elems = ce;
+    batch.g_elem_bytes = (uint32_t)gsz;
+    for (int64_t k = 0; k < cnt; ++k) {
+      const int64_t i = i0 + k;
+      ExpandTensor &t = batch.t[k];
+      t.numel = (uint64_t)l->numel[i];
+      t.first_chunk = next_chunk;
+      if (t.numel) {
+        t.x = static_cast<float *>(l->param[i]);
+        t.g = l->grad[i];
+        t.m = static_cast<float *>(l->m[i]);
+        t.v = hasv ? static_cast<float *>(l->v[i]) : nullptr;
+        const uintptr_t bits = (uintptr_t)t.x | (uintptr_t)t.m | (uintptr_t)t.v;
+        t.vec_ok = ((bits & 15) == 0) && (((uintptr_t)t.g & (bf16 ? 7 : 15)) == 0);
+      }
+      next_chunk += (uint32_t)((t.numel + ce - 1) / ce);
+    }
+    hipLaunchKernelGGL(expand_chunks_kernel, dim3((uint32_t)cnt), dim3(kThreads), 0, stream, batch, table, spans);
+    SWIFT_HIP(hipGetLastError());
+  }
+  if (next_chunk == 0) return SWIFT_OK;
+  // 2. pack the table by the mask (every entry of `packed` below next_chunk and the count are rewritten,
+  //    so nothing of an earlier call is read), 3. the undo over the packed table
+  const uint64_t n_slots = (uint64_t)next_chunk << tpc_shift;
+  uint64_t grid_cap = 0x7fffffffull;
+  const long per_cu = knobs().dmask_wgs_per_cu;
+  if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
+  hipLaunchKernelGGL(compact_chunks_kernel, dim3((uint32_t)l->n), dim3(kThreads), 0, stream,
+                     static_cast<const ChunkDesc *>(table), static_cast<const TensorChunks *>(spans), (uint32_t)l->n,
+                     device_mask, tpc_shift, packed, count);
+  SWIFT_HIP(hipGetLastError());
+  hipLaunchKernelGGL(pick_packed_kernel(hp->kind, true, bf16, false), dim3((uint32_t)std::min<uint64_t>(n_slots, grid_cap)),
+                     dim3((uint32_t)tune.block), lds_cap_bytes(info, tune), stream, static_cast<const ChunkDesc *>(packed),
+                     static_cast<const uint64_t *>(count), tpc_shift, c);
+  SWIFT_HIP(hipGetLastError());
+  return SWIFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // LAMB: step = moments + partial sums, norms, apply; undo = one launch.
 // Launch shapes (one wavefront per tile): U 16-byte vectors per lane in pass 1 (one partial sum per
 // tile) and in pass 3.  The environment variables exist for sweeps.
@@ -1167,6 +1363,12 @@ int swift_opt_step_dmask(const swift_tensor_list *list, const swift_hparams *hp,
 int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
                          void *hip_stream) {
   return guarded([&] { return opt_call(list, hp, nullptr, device_mask, true, true, hip_stream); });
+}
+
+int swift_opt_undo_dmask_noalloc(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
+                                 void *hip_stream) {
+  // no guarded(): nothing on this path allocates, so nothing can throw
+  return noalloc_undo_dmask(list, hp, device_mask, hip_stream);
 }
 
 int swift_opt_step_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
