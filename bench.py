@@ -13,12 +13,17 @@ resident in HBM before the clock starts:
   7. full Adam (coupled decay) step + undo
   8. full SGD-momentum step + undo (theta, g, m only)
 
-`value` is the number of parameter updates and parameter undos carried out per second of wall
-time over that whole pass (digests and mask derivation are in the time, not in the count).  The
-`roofline` object describes the dominant kernel, AdamW undo (launched twice per pass: selective and
-full list): mean algorithmic bytes per launch (28 per parameter with fp32 gradients: theta, g, m, v
-in; theta, m, v out) over the mean launch duration, measured with HIP events on the launching
-stream inside the timed region.
+`value` is the metric's quantity, Adam update-undo throughput: the parameters of the full list
+stepped by AdamW plus the parameters undone by its undo (2 x N) over the time of those two launches
+(item 6), measured with HIP events on the launching stream inside the timed pass and averaged over
+the timed passes.  `ms_per_step` is the wall time of a whole pass; `whole_pass` gives the number of
+parameter updates and undos of all optimizers over that wall time (digests and the mask derivation
+are in the time, not in the count).  The `roofline` object describes the dominant kernel, AdamW undo
+(launched twice per pass: selective and full list): mean algorithmic bytes per launch (28 per
+parameter with fp32 gradients: theta, g, m, v in; theta, m, v out) over the mean launch duration,
+from the same events.  The state lives in one arena laid out by swift_arena_layout's rule (--layout
+padded, the default); `roofline_framework_layout` is the same kernel timed in the same run on a state
+allocated the way a training framework allocates (one allocation per buffer, --layout framework).
 `cpu_baseline` times the fp64 CPU oracle on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--no-extras]
@@ -139,6 +144,8 @@ def main() -> int:
                          "of a tensor side by side and 4 KiB of skew between buffers (default); the same order in "
                          "separate torch allocations; all theta, then all g, m, v; or as a training framework would")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-second-layout", action="store_true",
+                    help="skip the second roofline measurement (the dominant kernel on a framework-style allocation)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the launches reported under 'extras' (a profile of such a run holds the timed pass only)")
     ap.add_argument("--cpu-sample", type=int, default=256 * 1024 * 1024)
@@ -329,7 +336,8 @@ def main() -> int:
     seg_all = {s: sorted(ev[k].elapsed_time(ev[k + 1]) for ev in all_events) for k, s in enumerate(segs)}
     seg_ms = {s: sum(v) / max(len(v), 1) for s, v in seg_all.items()}
     params_per_pass = sum(seg_params.values())
-    value = params_per_pass * args.steps / wall
+    whole_pass_value = params_per_pass * args.steps / wall
+    value = 2 * N / ((seg_ms["adamw_step"] + seg_ms["adamw_undo"]) * 1e-3)     # Adam update-undo: full step + full undo
     kernels = {}
     for s in segs:
         ms = seg_ms[s]
@@ -353,12 +361,18 @@ def main() -> int:
         "config": {"workload": f"{w.name}: {n_t} tensors, {N} params, fp32 theta/m/v, "
                                f"{'bf16' if bf16 else 'fp32'} grads, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident",
                    "pass": "digest, masked AdamW step, digest, mask, selective undo, full AdamW/Adam/SGDM step+undo",
-                   "params_updated_or_undone_per_pass": params_per_pass, "allocation_layout": args.layout,
+                   "value_is": "2 x params / (full-list AdamW step + full-list AdamW undo launch time), HIP events inside the timed pass",
+                   "allocation_layout": args.layout,
                    "storage": "fp32 state, arithmetic in fp64 registers"},
+        "whole_pass": {"params_updated_or_undone_per_pass": params_per_pass, "params_per_s": whole_pass_value,
+                       "note": "all optimizers' updates and undos over the wall time of the pass, digests and mask included in the time"},
         "roofline": {"bound": "hbm", "kernel": "opt_kernel<AdamW, undo>: mean of its 2 launches per pass "
                                                  "(selective undo of the marked tensors, full list)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
+                     "traffic": traffic,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary kept under profiles/ (counters "
+                                       "cannot be read from inside this process); null if it does not cover this workload",
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
                      "measured_copy_gb_per_s": copy_gbs, "frac_of_measured_copy": achieved / copy_gbs,
                      "gparams_per_s": dom_params / dom_ms / 1e6},
         "kernels": kernels,
@@ -367,6 +381,48 @@ def main() -> int:
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(w, state, hp_dicts["adamw"], args.cpu_sample)
+    if not args.no_second_layout and args.layout != "framework":
+        # The same two launches of the dominant kernel on a state allocated as a training framework allocates it:
+        # every buffer an allocation of its own (theta at model build, gradients in backward order, m and v at
+        # the first optimizer step).  Same values, same kernels; only the addresses differ.
+        del tl_adam, tl_sgdm, bufs, groups, state
+        B.swift_cache_trim(0)
+        torch.cuda.empty_cache()
+        log("[bench] second layout: drawing the state in framework-style allocations ...")
+        state = synth.make_state(w, "cuda:0", with_v=True, layout="framework")
+        tl_fw = B.TensorList(state.theta, state.grad, state.m, state.v)
+        names = ("adamw_step_masked", "adamw_undo_selective", "adamw_step", "adamw_undo")
+
+        def fw_pass(events=None):
+            def mark():
+                if events is not None:
+                    e = torch.cuda.Event(enable_timing=True)
+                    e.record()
+                    events.append(e)
+            mark()
+            B.swift_opt_step(tl_fw, hp_w, host_mask=mask); mark()
+            B.swift_opt_undo(tl_fw, hp_w, host_mask=mask); mark()
+            B.swift_opt_step(tl_fw, hp_w); mark()
+            B.swift_opt_undo(tl_fw, hp_w); mark()
+        for _ in range(max(args.warmup, 2)):
+            fw_pass()
+        fw_events = []
+        for _ in range(max(3, min(args.steps, 10))):
+            ev = []
+            fw_pass(ev)
+            fw_events.append(ev)
+        torch.cuda.synchronize()
+        fw_ms = {s_: sum(ev[k].elapsed_time(ev[k + 1]) for ev in fw_events) / len(fw_events) for k, s_ in enumerate(names)}
+        fw_dom_ms = (fw_ms["adamw_undo_selective"] + fw_ms["adamw_undo"]) / 2
+        fw_achieved = dom_bytes / fw_dom_ms / 1e6
+        out["roofline_framework_layout"] = {
+            "bound": "hbm", "kernel": out["roofline"]["kernel"], "allocation_layout": "framework",
+            "achieved": fw_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fw_achieved / HBM_PEAK_GBS,
+            "traffic": None, "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": fw_dom_ms,
+            "value_params_per_s": 2 * N / ((fw_ms["adamw_step"] + fw_ms["adamw_undo"]) * 1e-3),
+            "kernels_ms": {k: round(v, 4) for k, v in fw_ms.items()}}
+        log(f"[bench] framework layout: AdamW undo {fw_achieved:.0f} GB/s ({fw_achieved / HBM_PEAK_GBS:.3f} of peak), "
+            f"step+undo {out['roofline_framework_layout']['value_params_per_s'] / 1e9:.1f} G params/s")
     print(json.dumps(out), flush=True)
     return 0
 

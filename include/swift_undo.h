@@ -111,7 +111,7 @@ typedef struct {
  * Placement advice (throughput only, never correctness): on MI355X the kernels run 2-10 % faster when
  * param[i], grad[i], m[i], v[i] of a tensor do NOT all start at the same address modulo 8 KiB, e.g. when
  * consecutive buffers of an arena are an odd multiple of 2 KiB apart; allocators that hand out buffers at
- * 2 MiB granularity produce the slow case.
+ * 2 MiB granularity produce the slow case.  swift_arena_layout computes such a placement.
  * param_bf16 (nullable array; not from the paper): mixed-precision training keeps a bfloat16 copy of
  * the parameters next to the binary32 master weights.  If the array is given, swift_opt_step and
  * swift_opt_undo (host- and device-mask forms) also write, for every tensor they touch, the bfloat16
@@ -295,6 +295,19 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
 int swift_logging_groups(int64_t n_machines, const double *compute_time, const double *message_bytes,
                          double checkpoint_interval, double bandwidth, double storage_limit, int parallel_recovery,
                          int32_t *group_of, double *storage_out, double *recovery_out);
+
+/* Placement helper, host arithmetic only: byte offsets for the state of n tensors inside ONE device allocation
+ * (the caller allocates total_bytes, 256-byte aligned, and carves the buffers out of it), laid out so that the
+ * kernels reach their best bandwidth.  offsets[i * S + k] is the offset of stream k of tensor i, with S = 4
+ * streams (theta, gradient, m, v) if with_v is non-zero, else 3 (theta, gradient, m); the four buffers of a
+ * tensor are adjacent, tensor after tensor.  A buffer of 1 MiB or more occupies its size rounded up to 8 KiB plus
+ * 2 KiB, so that consecutive buffers start an odd multiple of 2 KiB apart and theta, g, m, v of a tensor begin in
+ * four different quarters of an 8 KiB window; smaller buffers are rounded up to 256 bytes.  Why: a tile of the
+ * update kernels reads the same offset of all four buffers at once, and when these start at the same address
+ * modulo 8 KiB (what an allocator with 2 MiB granularity produces) MI355X serves them 2-10 % slower.  Every
+ * offset is a multiple of 256.  numel, offsets: HOST (offsets: n * S entries); total_bytes: HOST, nullable. */
+int swift_arena_layout(int64_t n, const int64_t *numel, int32_t grad_dtype, int32_t with_v, int64_t *offsets,
+                       int64_t *total_bytes);
 
 /* What the library holds: number of cached lists and bytes of device memory behind them (either
  * pointer may be NULL).  HOST. */

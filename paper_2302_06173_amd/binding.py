@@ -78,7 +78,7 @@ _lib.swift_last_error.argtypes = []
 _lib.swift_last_error.restype = ctypes.c_char_p
 
 EXPORTS = ("swift_opt_step", "swift_opt_undo", "swift_opt_step_dmask", "swift_opt_undo_dmask",
-           "swift_opt_undo_dmask_noalloc", "swift_cache_stats", "swift_cache_trim",
+           "swift_opt_undo_dmask_noalloc", "swift_cache_stats", "swift_cache_trim", "swift_arena_layout",
            "swift_lamb_step", "swift_lamb_undo", "swift_opt_step_digest", "swift_opt_undo_digest",
            "swift_tracker_create", "swift_tracker_begin", "swift_tracker_step", "swift_tracker_marks",
            "swift_tracker_undo", "swift_tracker_destroy",
@@ -380,6 +380,22 @@ def swift_logging_groups(compute_time: Sequence[float], message_bytes: Sequence[
     _check(_lib.swift_logging_groups(n, R, M, float(checkpoint_interval), float(bandwidth), float(storage_limit),
                                      1 if parallel_recovery else 0, out, ctypes.byref(storage), ctypes.byref(recovery)))
     return list(out[:n]), storage.value, recovery.value
+
+
+_lib.swift_arena_layout.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, ctypes.c_int32,
+                                    ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+_lib.swift_arena_layout.restype = ctypes.c_int
+
+
+def swift_arena_layout(numel: Sequence[int], grad_bf16: bool = False, with_v: bool = True):
+    """Byte offsets (one row [theta, g, m(, v)] per tensor) and the total size of an arena that holds the state."""
+    n, s = len(numel), 4 if with_v else 3
+    sizes = (ctypes.c_int64 * max(n, 1))(*numel)
+    offs = (ctypes.c_int64 * max(n * s, 1))()
+    total = ctypes.c_int64()
+    _check(_lib.swift_arena_layout(n, sizes, SWIFT_BF16 if grad_bf16 else SWIFT_F32, 1 if with_v else 0, offs,
+                                   ctypes.byref(total)))
+    return [list(offs[i * s:(i + 1) * s]) for i in range(n)], total.value
 
 
 def swift_cache_stats():

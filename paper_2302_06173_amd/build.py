@@ -28,11 +28,26 @@ FLAGS = [
 ]
 
 
+STAMP = LIB + ".srchash"      # sha256 of the sources and flags the library beside it was built from
+
+
+def source_hash(extra_flags=()) -> str:
+    import hashlib
+    h = hashlib.sha256()
+    h.update("\0".join([*FLAGS, *extra_flags]).encode())
+    for p in SOURCES + HEADERS + [EXAMPLE_SRC]:
+        with open(p, "rb") as fh:
+            h.update(b"\0" + os.path.basename(p).encode() + b"\0" + fh.read())
+    return h.hexdigest()
+
+
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    """True if there is no library, or it was built from other sources than the ones in the tree (file
+    times play no part: a copied tree keeps contents, not times)."""
+    if not os.path.exists(LIB) or not os.path.exists(EXAMPLE) or not os.path.exists(STAMP):
         return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS + [EXAMPLE_SRC]) or not os.path.exists(EXAMPLE)
+    with open(STAMP) as fh:
+        return fh.read().strip() != source_hash()
 
 
 def build(force: bool = True, extra_flags=()) -> str:
@@ -51,16 +66,17 @@ def build(force: bool = True, extra_flags=()) -> str:
         print(err, file=sys.stderr)
     os.replace(tmp, LIB)
     build_example()
+    with open(STAMP, "w") as fh:
+        fh.write(source_hash(extra_flags) + "\n")
     return LIB
 
 
 def ensure_built() -> str:
-    """Build only if no library is there (tests, the smoke run and the benchmark call this; they never
-    rebuild what exists, so build again yourself after changing a source)."""
-    if not os.path.exists(LIB):
+    """What tests, the smoke run and the benchmark call: loads what is built, and builds (hipcc cross-compiles
+    without a GPU) only if there is no library or the library was built from other sources than the tree holds,
+    so that nothing is ever tested against a stale binary."""
+    if is_stale():
         build()
-    elif not os.path.exists(EXAMPLE):
-        build_example()
     return LIB
 
 

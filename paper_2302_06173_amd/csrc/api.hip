@@ -1672,6 +1672,27 @@ int swift_logging_groups(int64_t n_machines, const double *compute_time, const d
   });
 }
 
+int swift_arena_layout(int64_t n, const int64_t *numel, int32_t grad_dtype, int32_t with_v, int64_t *offsets,
+                       int64_t *total_bytes) {
+  if (n < 0 || n > (int64_t)0x7fffffff || (n > 0 && (!numel || !offsets)))
+    return fail(SWIFT_EINVAL, "arena_layout: bad n, numel or offsets");
+  if (grad_dtype != SWIFT_F32 && grad_dtype != SWIFT_BF16) return fail(SWIFT_EINVAL, "arena_layout: unknown gradient dtype %d", grad_dtype);
+  const int streams = with_v ? 4 : 3;
+  int64_t off = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    if (numel[i] < 0 || numel[i] > kMaxNumel) return fail(SWIFT_EINVAL, "arena_layout: numel[%lld] is negative or beyond 2^40", (long long)i);
+    for (int k = 0; k < streams; ++k) {
+      const int64_t bytes = numel[i] * ((k == 1 && grad_dtype == SWIFT_BF16) ? 2 : 4);
+      offsets[i * streams + k] = off;
+      // 1 MiB and more: round up to 8 KiB, then 2 KiB on top, so that consecutive buffers start an odd multiple
+      // of 2 KiB apart; smaller buffers are only kept 256-byte aligned
+      off += bytes < (1 << 20) ? (bytes + 255) / 256 * 256 : (bytes + 8191) / 8192 * 8192 + 2048;
+    }
+  }
+  if (total_bytes) *total_bytes = off;
+  return SWIFT_OK;
+}
+
 int swift_cache_stats(int64_t *n_lists, int64_t *device_bytes) {
   int64_t n = 0, bytes = 0;
   {

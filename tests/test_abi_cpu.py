@@ -238,3 +238,26 @@ def test_header_is_plain_c(tmp_path):
                    '  return swift_opt_step(&l, &hp, 0, 0) + (int)swift_digest_count(0, 0, 0); }\n')
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                            "-I", os.path.join(ROOT, "include"), str(src)])
+
+
+def test_arena_layout_is_host_arithmetic_and_matches_the_benchmark_state(B):
+    """swift_arena_layout: offsets are 256-byte aligned and disjoint, large buffers start an odd multiple of 2 KiB
+    apart, and the rule is the one the synthetic states are laid out with."""
+    from paper_2302_06173_amd import synth
+    for shapes, bf16, with_v in ((synth.bert_large_shapes(), False, True), (synth.gpt2_xl_shapes(), True, True),
+                                 (synth.vit_128_32_shapes(), False, False), ([(0,), (3,), (1 << 18,), (262145,)], False, True)):
+        numel = [synth.numel(s) for s in shapes]
+        rows, total = B.swift_arena_layout(numel, grad_bf16=bf16, with_v=with_v)
+        off = 0
+        for n, row in zip(numel, rows):
+            assert len(row) == (4 if with_v else 3)
+            for k, o in enumerate(row):
+                nbytes = n * (2 if (bf16 and k == 1) else 4)
+                assert o == off and o % 256 == 0
+                off += synth.padded_extent(nbytes)
+                if nbytes >= 1 << 20:
+                    assert (off - o) % 4096 == 2048            # an odd multiple of 2 KiB to the next buffer
+        assert total == off
+    assert B.swift_arena_layout([], with_v=True) == ([], 0)
+    with pytest.raises(B.SwiftError):
+        B.swift_arena_layout([-1])
