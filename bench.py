@@ -302,12 +302,13 @@ def main() -> int:
     groups = [B.TensorList([state.theta[i] for i in g], [state.grad[i] for i in g], [state.m[i] for i in g],
                            [state.v[i] for i in g]) for g in ids]
     tracker = B.Tracker(n_t)
+    id_arrays = [B.Tracker.ids(g) for g in ids]
 
     hp_a = hps["adam"]       # Adam, not AdamW: the roofline kernel's launches stay those of the timed pass
 
     def tracked_step_and_undo():
         tracker.begin(t_step)
-        for g, tl_g in zip(ids, groups):
+        for g, tl_g in zip(id_arrays, groups):
             tracker.step(tl_g, g, hp_a)
         tracker.undo(tl_adam, hp_a)
     extra(f"adam_tracked_step_in_{len(groups)}_groups_plus_undo", tracked_step_and_undo, 24 + g_bytes, 2 * N)

@@ -191,7 +191,7 @@ int swift_opt_undo_dmask_noalloc(const swift_tensor_list *list, const swift_hpar
  * swift_mask_from_digests tell which tensors hold stepped bits (the role of the paper's per-parameter
  * "updated" flag, Implementation, "Update-undo").  Entries of unmarked tensors are left alone.  Every
  * tensor must have fewer than 2^32 elements.  digests_device: DEVICE, 3n (2n for SGDM) entries, 8-byte
- * aligned.  The call keeps per-list scratch (24 bytes per chunk): calls on one list must not overlap. */
+ * aligned.  The call keeps per-list scratch (24 bytes per 256 elements): calls on one list must not overlap. */
 int swift_opt_step_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
                           uint64_t *digests_device, void *hip_stream);
 int swift_opt_undo_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
@@ -210,7 +210,7 @@ int swift_opt_undo_digest(const swift_tensor_list *list, const swift_hparams *hp
  * hp->kind must be SWIFT_LAMB; beta1, beta2, eps as for Adam.  norms_device: DEVICE, 2*n doubles, 8-byte
  * aligned.  If 1 - eta q lambda happens to be 0 for a tensor the undo yields Inf/NaN there (q lives on
  * the device, so the host cannot refuse the call).  The step keeps per-list scratch for the partial
- * sums (16 bytes per 1,024 elements): calls on the same list must not overlap in time. */
+ * sums (16 bytes per 256 elements): calls on the same list must not overlap in time. */
 int swift_lamb_step(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
                     double *norms_device, void *hip_stream);
 int swift_lamb_undo(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,

@@ -323,11 +323,16 @@ class Tracker:
     def begin(self, step: int) -> None:
         _check(_lib.swift_tracker_begin(self._h, int(step)))
 
-    def step(self, group: TensorList, tensor_ids: Sequence[int], hp: SwiftHparams, grad_ready_event=None,
+    @staticmethod
+    def ids(tensor_ids: Sequence[int]):
+        """The ids of a group marshalled once (a loop that steps the same groups every iteration keeps these)."""
+        return (ctypes.c_int64 * max(len(tensor_ids), 1))(*tensor_ids)
+
+    def step(self, group: TensorList, tensor_ids, hp: SwiftHparams, grad_ready_event=None,
              stream=None) -> None:
-        if len(tensor_ids) != group.n:
+        if len(tensor_ids) != max(group.n, 1) and len(tensor_ids) != group.n:
             raise ValueError("one id per tensor of the group")
-        ids = (ctypes.c_int64 * max(group.n, 1))(*tensor_ids)
+        ids = tensor_ids if isinstance(tensor_ids, ctypes.Array) else self.ids(tensor_ids)
         ev = None
         if grad_ready_event is not None:
             ev = grad_ready_event.cuda_event if isinstance(grad_ready_event, torch.cuda.Event) else int(grad_ready_event)

@@ -15,6 +15,8 @@ SOURCES = [os.path.join(PKG, "csrc", "api.hip")]
 HEADERS = [os.path.join(PKG, "csrc", h) for h in
            ("opt_kernels.hpp", "digest_kernels.hpp", "lamb_kernels.hpp", "fused_kernels.hpp", "logging_groups.hpp")] + \
           [os.path.join(ROOT, "include", "swift_undo.h")]
+MICROBENCH_SRC = os.path.join(PKG, "csrc", "alu_issue_rates.hip")
+MICROBENCH = os.path.join(PKG, "alu_issue_rates.bin")
 EXAMPLE_SRC = os.path.join(PKG, "csrc", "example_undo_roundtrip.c")
 EXAMPLE = os.path.join(PKG, "example_undo_roundtrip.bin")
 
@@ -35,7 +37,7 @@ def source_hash(extra_flags=()) -> str:
     import hashlib
     h = hashlib.sha256()
     h.update("\0".join([*FLAGS, *extra_flags]).encode())
-    for p in SOURCES + HEADERS + [EXAMPLE_SRC]:
+    for p in SOURCES + HEADERS + [EXAMPLE_SRC, MICROBENCH_SRC]:
         with open(p, "rb") as fh:
             h.update(b"\0" + os.path.basename(p).encode() + b"\0" + fh.read())
     return h.hexdigest()
@@ -66,6 +68,7 @@ def build(force: bool = True, extra_flags=()) -> str:
         print(err, file=sys.stderr)
     os.replace(tmp, LIB)
     build_example()
+    build_microbench()
     with open(STAMP, "w") as fh:
         fh.write(source_hash(extra_flags) + "\n")
     return LIB
@@ -78,6 +81,18 @@ def ensure_built() -> str:
     if is_stale():
         build()
     return LIB
+
+
+def build_microbench() -> str:
+    """The instruction-issue microbenchmark (a measurement aid, stand-alone, not linked to the library)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = MICROBENCH + f".tmp{os.getpid()}"
+    res = subprocess.run([hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-o", tmp, MICROBENCH_SRC],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on the microbenchmark:\n" + res.stderr)
+    os.replace(tmp, MICROBENCH)
+    return MICROBENCH
 
 
 def build_example() -> str:

@@ -73,7 +73,7 @@ long env_long(const char *name, long dflt) {
 constexpr long kUnset = -1;
 struct Knobs {
   long tile_u, tile_block, waves_per_cu, chunk_elems, dmask_wgs_per_cu;
-  long digest_chunk_elems, copy_u, copy_waves_per_cu;
+  long digest_chunk_elems, digest_waves_per_cu, copy_u, copy_waves_per_cu;
   long lamb_u1, lamb_u3, lamb_waves_p1, lamb_waves_p3, fused_u, fused_waves_per_cu;
 };
 
@@ -85,6 +85,7 @@ Knobs read_knobs() {
   k.chunk_elems = env_long("SWIFT_CHUNK_ELEMS", 0);
   k.dmask_wgs_per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
   k.digest_chunk_elems = env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0);
+  k.digest_waves_per_cu = env_long("SWIFT_DIGEST_WAVES_PER_CU", SWIFT_DIGEST_WAVES_PER_CU);
   k.copy_u = env_long("SWIFT_COPY_U", SWIFT_COPY_U);
   k.copy_waves_per_cu = env_long("SWIFT_COPY_WAVES_PER_CU", SWIFT_COPY_WAVES_PER_CU);
   k.lamb_u1 = env_long("SWIFT_LAMB_U1", SWIFT_LAMB_U1);
@@ -360,11 +361,13 @@ struct Tuning {
   int u, block, waves_per_cu;
 };
 
-Tuning opt_tuning(int kind, bool bf16) {
+Tuning opt_tuning(int kind, bool bf16, bool undo) {
   // Measured optima: the fewer bytes a wavefront moves (SGDM has 3 streams in and 2 out instead of
-  // 4 and 3; bf16 gradients halve one stream), the more wavefronts a compute unit wants.
-  const int waves = kind == SWIFT_SGDM ? (bf16 ? SWIFT_DEFAULT_WAVES_PER_CU_SGDM + 1 : SWIFT_DEFAULT_WAVES_PER_CU_SGDM)
-                                       : (bf16 ? SWIFT_DEFAULT_WAVES_PER_CU + 1 : SWIFT_DEFAULT_WAVES_PER_CU);
+  // 4 and 3; bf16 gradients halve one stream), the more wavefronts a compute unit wants; with bf16
+  // gradients the Adam-family undo wants two more than the step (GPT-2 list: 6.30 against 6.56 ms).
+  int waves;
+  if (kind == SWIFT_SGDM) waves = SWIFT_DEFAULT_WAVES_PER_CU_SGDM + (bf16 ? 1 : 0);
+  else waves = SWIFT_DEFAULT_WAVES_PER_CU + (bf16 ? (undo ? 3 : 1) : 0);
   const Knobs k = knobs();
   return Tuning{(int)k.tile_u, (int)k.tile_block, k.waves_per_cu == kUnset ? waves : (int)k.waves_per_cu};
 }
@@ -718,7 +721,7 @@ int opt_prepare(const swift_tensor_list *l, const swift_hparams *hp, const uint8
   SWIFT_HIP(hipGetDevice(&dev));
   if ((rc = device_info(dev, &out->info))) return rc;
   const bool bf16 = hp->grad_dtype == SWIFT_BF16, xb = l->param_bf16 != nullptr;
-  out->tune = opt_tuning(hp->kind, bf16);
+  out->tune = opt_tuning(hp->kind, bf16, undo);
   if (want_dmask) out->tune.u = SWIFT_DEFAULT_U, out->tune.block = SWIFT_DEFAULT_BLOCK;     // the only packed-table shape
   out->kernel = pick_kernel(out->tune, hp->kind, undo, bf16, xb);
   if (!out->kernel)
@@ -925,7 +928,7 @@ int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, cons
   TensorChunks *spans = reinterpret_cast<TensorChunks *>(sb + kNoallocSpansOff);
   uint64_t *count = reinterpret_cast<uint64_t *>(sb + kNoallocCountOff);
   const hipStream_t stream = static_cast<hipStream_t>(stream_);
-  Tuning tune = opt_tuning(hp->kind, bf16);
+  Tuning tune = opt_tuning(hp->kind, bf16, true);
   tune.u = SWIFT_DEFAULT_U, tune.block = SWIFT_DEFAULT_BLOCK;
   const uint32_t tile_elems = (uint32_t)tune.u * (uint32_t)tune.block * 4u;
   const uint32_t tpc_shift = shift_for(tile_elems, ce);
@@ -1062,7 +1065,7 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
   const uint64_t slotsu = (uint64_t)plan->n_chunks << su;
   const Tuning t1{u1, 64, (int)kn.lamb_waves_p1};
   const Tuning t3{u3, 64, (int)kn.lamb_waves_p3};
-  const Tuning tu = opt_tuning(SWIFT_ADAMW, bf16);
+  const Tuning tu = opt_tuning(SWIFT_ADAMW, bf16, true);
   const ChunkDesc *chunks = static_cast<const ChunkDesc *>(plan->chunks());
   if (undo) {
     if (plan->n_chunks == 0) return SWIFT_OK;
@@ -1181,7 +1184,7 @@ int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_
   std::shared_ptr<Plan> plan;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if ((rc = build_opt_plan(l, hp, host_mask, dev, stream, &plan))) return rc;
-  Tuning tune = opt_tuning(hp->kind, bf16);
+  Tuning tune = opt_tuning(hp->kind, bf16, undo);
   tune.u = (int)knobs().fused_u;
   tune.block = 64;
   // the digest arithmetic makes this kernel ALU-heavy: more resident wavefronts overlap it with memory
@@ -1419,7 +1422,8 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
     SWIFT_HIP(hipGetLastError());
     if (plan->n_chunks == 0) return SWIFT_OK;
     const uint32_t grid = plan->n_chunks;                        // one workgroup per chunk
-    hipLaunchKernelGGL(digest_kernel, dim3(grid), dim3(kThreads), 0, stream, static_cast<const DigestDesc *>(plan->descs()),
+    const Tuning dtune{1, kThreads, (int)knobs().digest_waves_per_cu};
+    hipLaunchKernelGGL(digest_kernel, dim3(grid), dim3(kThreads), lds_cap_bytes(info, dtune), stream, static_cast<const DigestDesc *>(plan->descs()),
                        static_cast<const ChunkRef *>(plan->chunks()), plan->n_chunks, plan->chunk_elems,
                        (uint64_t)shard_elems,
                        reinterpret_cast<unsigned long long *>(out_device));

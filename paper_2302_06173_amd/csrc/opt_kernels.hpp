@@ -27,6 +27,9 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #endif
 // Tuning defaults, all measured on MI355X with the 7 B-parameter list (wavefronts per compute unit
 // are enforced through unused dynamic LDS).  Each can be overridden on the compiler's command line.
+#ifndef SWIFT_DIGEST_WAVES_PER_CU
+#define SWIFT_DIGEST_WAVES_PER_CU 0     // digest kernel: residency cap (0 = none)
+#endif
 #ifndef SWIFT_DIGEST_CHUNK
 #define SWIFT_DIGEST_CHUNK 65536        // digest kernel: words per workgroup (large inputs)
 #endif
@@ -49,16 +52,16 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #define SWIFT_FUSED_WAVES_PER_CU 24     // step/undo fused with the digest
 #endif
 #ifndef SWIFT_LAMB_U1
-#define SWIFT_LAMB_U1 4                 // LAMB pass 1: vectors per lane (tile = U * 256 elements)
+#define SWIFT_LAMB_U1 1                 // LAMB pass 1: vectors per lane (tile = U * 256 elements, one partial sum pair per tile)
 #endif
 #ifndef SWIFT_LAMB_U3
 #define SWIFT_LAMB_U3 1                 // LAMB pass 3
 #endif
 #ifndef SWIFT_LAMB_WAVES_P1
-#define SWIFT_LAMB_WAVES_P1 6           // LAMB pass 1 (U = 4): wavefronts per CU
+#define SWIFT_LAMB_WAVES_P1 14          // LAMB pass 1 (U = 1): wavefronts per CU
 #endif
 #ifndef SWIFT_LAMB_WAVES_P3
-#define SWIFT_LAMB_WAVES_P3 24          // LAMB pass 3 (3 streams in, 1 out)
+#define SWIFT_LAMB_WAVES_P3 20          // LAMB pass 3 (3 streams in, 1 out)
 #endif
 #ifndef SWIFT_DEFAULT_DMASK_WGS_PER_CU
 #define SWIFT_DEFAULT_DMASK_WGS_PER_CU 16384

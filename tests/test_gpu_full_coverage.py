@@ -247,8 +247,8 @@ def _release_at_the_end():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("stage", STAGES)                                     # varies fastest: one state per workload
 @pytest.mark.parametrize("name", ["gpt2_xl_adamw_bf16g", "llama7b_adamw"])
-@pytest.mark.parametrize("stage", STAGES)
 def test_every_element_against_the_oracle(B, synth, name, stage, capsys):
     flow = _flow(B, synth, name)
     flow.advance_to(stage)
