@@ -72,7 +72,7 @@ long env_long(const char *name, long dflt) {
 // every call (a sweep that changes the variables between calls).  kUnset = "use the built-in default".
 constexpr long kUnset = -1;
 struct Knobs {
-  long tile_u, tile_block, waves_per_cu, chunk_elems, dmask_wgs_per_cu;
+  long tile_u, tile_block, waves_per_cu, chunk_elems, dmask_wgs_per_cu, dmask_queue, dmask_counters, dmask_queue_waves;
   long digest_chunk_elems, digest_waves_per_cu, copy_u, copy_waves_per_cu;
   long lamb_u1, lamb_u3, lamb_waves_p1, lamb_waves_p3, fused_u, fused_waves_per_cu;
 };
@@ -84,6 +84,9 @@ Knobs read_knobs() {
   k.waves_per_cu = env_long("SWIFT_WAVES_PER_CU", kUnset);
   k.chunk_elems = env_long("SWIFT_CHUNK_ELEMS", 0);
   k.dmask_wgs_per_cu = env_long("SWIFT_DMASK_WGS_PER_CU", SWIFT_DEFAULT_DMASK_WGS_PER_CU);
+  k.dmask_queue = env_long("SWIFT_DMASK_QUEUE", SWIFT_DMASK_QUEUE);
+  k.dmask_counters = env_long("SWIFT_DMASK_COUNTERS", SWIFT_DMASK_COUNTERS);
+  k.dmask_queue_waves = env_long("SWIFT_DMASK_QUEUE_WAVES_PER_CU", SWIFT_DMASK_QUEUE_WAVES_PER_CU);
   k.digest_chunk_elems = env_long("SWIFT_DIGEST_CHUNK_ELEMS", 0);
   k.digest_waves_per_cu = env_long("SWIFT_DIGEST_WAVES_PER_CU", SWIFT_DIGEST_WAVES_PER_CU);
   k.copy_u = env_long("SWIFT_COPY_U", SWIFT_COPY_U);
@@ -631,6 +634,9 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
 
 typedef void (*OptKernel)(const ChunkDesc *, uint64_t, uint32_t, const OptConsts);
 typedef void (*OptPackedKernel)(const ChunkDesc *, const uint64_t *, uint32_t, const OptConsts);
+typedef void (*OptQueueKernel)(const ChunkDesc *, const uint64_t *, uint32_t, const OptConsts, unsigned int *, uint32_t);
+constexpr long kQueueMaxCounters = 256;               // = kThreads: compact_chunks_kernel clears them with one workgroup
+constexpr size_t kQueueCounterBytes = kQueueMaxCounters * 128;      // tile counters, 128 bytes apart, behind the slot count
 
 #define SWIFT_PICK_KIND(KERNEL, U_, B_)                                                                        \
   switch (kind) {                                                                                              \
@@ -661,6 +667,9 @@ OptKernel pick_kernel(const Tuning &t, int kind, bool undo, bool bf16, bool xb) 
 OptPackedKernel pick_packed_kernel(int kind, bool undo, bool bf16, bool xb) {
   SWIFT_PICK_KIND(opt_packed_kernel, SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK)
 }
+OptQueueKernel pick_queue_kernel(int kind, bool undo, bool bf16, bool xb) {
+  SWIFT_PICK_KIND(opt_queue_kernel, SWIFT_DEFAULT_U, SWIFT_DEFAULT_BLOCK)
+}
 #undef SWIFT_PICK_KIND
 #undef SWIFT_PICK_FLAGS
 #undef SWIFT_PICK_XB
@@ -679,7 +688,7 @@ int packed_prepare(Plan &plan, hipStream_t stream) {
   const size_t table_off = (spans.size() * sizeof(TensorChunks) + 255) & ~size_t(255);
   const size_t count_off = table_off + std::max<size_t>(plan.n_chunks, 1) * sizeof(ChunkDesc);
   void *mem = nullptr;
-  SWIFT_HIP(hipMalloc(&mem, count_off + 256));
+  SWIFT_HIP(hipMalloc(&mem, count_off + 256 + kQueueCounterBytes));
   hipError_t e = hipMemcpy(mem, spans.data(), spans.size() * sizeof(TensorChunks), hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     (void)hipFree(mem);
@@ -688,7 +697,7 @@ int packed_prepare(Plan &plan, hipStream_t stream) {
   plan.packed_table_off = table_off;
   plan.packed_count_off = count_off;
   plan.packed_mem = mem;
-  plan.dev_bytes += count_off + 256;
+  plan.dev_bytes += count_off + 256 + kQueueCounterBytes;
   return SWIFT_OK;
 }
 
@@ -701,6 +710,7 @@ struct OptLaunch {
   Tuning tune;
   OptKernel kernel = nullptr;
   OptPackedKernel packed_kernel = nullptr;
+  OptQueueKernel queue_kernel = nullptr;
   std::shared_ptr<Plan> plan;
   const uint8_t *device_mask = nullptr;
   uint32_t n_tensors = 0, tpc_shift = 0;
@@ -736,9 +746,34 @@ int opt_prepare(const swift_tensor_list *l, const swift_hparams *hp, const uint8
   if (want_dmask) {
     if ((rc = packed_prepare(*out->plan, stream))) return rc;
     out->packed_kernel = pick_packed_kernel(hp->kind, undo, bf16, xb);
+    out->queue_kernel = pick_queue_kernel(hp->kind, undo, bf16, xb);
     out->device_mask = device_mask;
   }
   out->empty = false;
+  return SWIFT_OK;
+}
+
+// The update over a packed table, for both device-mask entry points.  Queue mode: a resident grid
+// (as many wavefronts as the residency cap lets a CU hold) that draws tiles from counters; strided
+// mode: one workgroup per slot up to a cap, striding beyond it.
+int launch_packed(OptPackedKernel packed_kernel, OptQueueKernel queue_kernel, const DeviceInfo &info, const Tuning &tune,
+                  uint64_t n_slots, uint32_t tpc_shift, const OptConsts &c, const ChunkDesc *packed, const uint64_t *count,
+                  unsigned int *counters, uint32_t log2c, hipStream_t stream) {
+  const Knobs kn = knobs();
+  if (kn.dmask_queue) {
+    Tuning qt = tune;
+    qt.waves_per_cu = (int)kn.dmask_queue_waves;
+    const uint64_t resident = (uint64_t)info.cus * (uint64_t)std::max(qt.waves_per_cu, 1);
+    hipLaunchKernelGGL(queue_kernel, dim3((uint32_t)std::min<uint64_t>(n_slots, resident)), dim3((uint32_t)tune.block),
+                       lds_cap_bytes(info, qt), stream, packed, count, tpc_shift, c, counters, log2c);
+    SWIFT_HIP(hipGetLastError());
+    return SWIFT_OK;
+  }
+  uint64_t grid_cap = 0x7fffffffull;
+  if (kn.dmask_wgs_per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)kn.dmask_wgs_per_cu;
+  hipLaunchKernelGGL(packed_kernel, dim3((uint32_t)std::min<uint64_t>(n_slots, grid_cap)), dim3((uint32_t)tune.block),
+                     lds_cap_bytes(info, tune), stream, packed, count, tpc_shift, c);
+  SWIFT_HIP(hipGetLastError());
   return SWIFT_OK;
 }
 
@@ -761,17 +796,16 @@ int opt_launch(const OptLaunch &L, hipStream_t stream) {
   char *pm = static_cast<char *>(plan.packed_mem);
   ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(pm + plan.packed_table_off);
   uint64_t *count = reinterpret_cast<uint64_t *>(pm + plan.packed_count_off);
-  uint64_t grid_cap = 0x7fffffffull;
-  const long per_cu = knobs().dmask_wgs_per_cu;
-  if (per_cu > 0) grid_cap = (uint64_t)L.info.cus * (uint64_t)per_cu;
+  unsigned int *counters = reinterpret_cast<unsigned int *>(pm + plan.packed_count_off + 256);
+  const Knobs kn = knobs();
+  uint32_t log2c = 0;
+  while ((2u << log2c) <= (uint32_t)std::min<long>(std::max<long>(kn.dmask_counters, 1), kQueueMaxCounters)) ++log2c;
   hipLaunchKernelGGL(compact_chunks_kernel, dim3(L.n_tensors), dim3(kThreads), 0, stream, table,
-                     reinterpret_cast<const TensorChunks *>(pm), L.n_tensors, L.device_mask, L.tpc_shift, packed, count);
+                     reinterpret_cast<const TensorChunks *>(pm), L.n_tensors, L.device_mask, L.tpc_shift, packed, count,
+                     counters, 1u << log2c);
   SWIFT_HIP(hipGetLastError());
-  hipLaunchKernelGGL(L.packed_kernel, dim3((uint32_t)std::min<uint64_t>(L.n_slots, grid_cap)), dim3((uint32_t)L.tune.block),
-                     lds_cap_bytes(L.info, L.tune), stream, static_cast<const ChunkDesc *>(packed),
-                     static_cast<const uint64_t *>(count), L.tpc_shift, L.c);
-  SWIFT_HIP(hipGetLastError());
-  return SWIFT_OK;
+  return launch_packed(L.packed_kernel, L.queue_kernel, L.info, L.tune, L.n_slots, L.tpc_shift, L.c, packed, count, counters,
+                       log2c, stream);
 }
 
 int opt_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask,
@@ -794,7 +828,7 @@ constexpr size_t kNoallocTableOff = 0;
 constexpr size_t kNoallocPackedOff = kNoallocTableOff + (size_t)kNoallocMaxChunks * sizeof(ChunkDesc);
 constexpr size_t kNoallocSpansOff = kNoallocPackedOff + (size_t)kNoallocMaxChunks * sizeof(ChunkDesc);
 constexpr size_t kNoallocCountOff = kNoallocSpansOff + (size_t)kNoallocMaxTensors * sizeof(TensorChunks);
-constexpr size_t kNoallocBytes = kNoallocCountOff + 256;
+constexpr size_t kNoallocBytes = kNoallocCountOff + 256 + kQueueCounterBytes;
 
 // Every GPU the library runs on holds its own copy of this array until the process ends.  In host
 // code the name is only a handle for hipGetSymbolAddress; kernels get the address that call returned.
@@ -965,18 +999,15 @@ int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, cons
   // 2. pack the table by the mask (every entry of `packed` below next_chunk and the count are rewritten,
   //    so nothing of an earlier call is read), 3. the undo over the packed table
   const uint64_t n_slots = (uint64_t)next_chunk << tpc_shift;
-  uint64_t grid_cap = 0x7fffffffull;
-  const long per_cu = knobs().dmask_wgs_per_cu;
-  if (per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)per_cu;
+  unsigned int *counters = reinterpret_cast<unsigned int *>(sb + kNoallocCountOff + 256);
+  uint32_t log2c = 0;
+  while ((2u << log2c) <= (uint32_t)std::min<long>(std::max<long>(knobs().dmask_counters, 1), kQueueMaxCounters)) ++log2c;
   hipLaunchKernelGGL(compact_chunks_kernel, dim3((uint32_t)l->n), dim3(kThreads), 0, stream,
                      static_cast<const ChunkDesc *>(table), static_cast<const TensorChunks *>(spans), (uint32_t)l->n,
-                     device_mask, tpc_shift, packed, count);
+                     device_mask, tpc_shift, packed, count, counters, 1u << log2c);
   SWIFT_HIP(hipGetLastError());
-  hipLaunchKernelGGL(pick_packed_kernel(hp->kind, true, bf16, false), dim3((uint32_t)std::min<uint64_t>(n_slots, grid_cap)),
-                     dim3((uint32_t)tune.block), lds_cap_bytes(info, tune), stream, static_cast<const ChunkDesc *>(packed),
-                     static_cast<const uint64_t *>(count), tpc_shift, c);
-  SWIFT_HIP(hipGetLastError());
-  return SWIFT_OK;
+  return launch_packed(pick_packed_kernel(hp->kind, true, bf16, false), pick_queue_kernel(hp->kind, true, bf16, false), info, tune,
+                       n_slots, tpc_shift, c, packed, count, counters, log2c, stream);
 }
 
 // ------------------------------------------------------------------------------------------

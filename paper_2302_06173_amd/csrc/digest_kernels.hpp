@@ -170,11 +170,12 @@ struct TensorChunks {
 // chunks of unmarked tensors before it and T = chunks of all marked tensors, a marked tensor's
 // entries are copied to packed[A ...) (list order is kept) and an unmarked tensor writes empty
 // entries to packed[T + I ...): every entry of `packed` is written, so nothing of an earlier call
-// survives.  *n_slots_out = T << tpc_shift, the number of tile slots the packed table holds.
+// survives.  *n_slots_out = T << tpc_shift, the number of tile slots the packed table holds.  The
+// kernel also clears the n_counters (at most kThreads) tile counters that opt_queue_kernel draws from.
 __global__ void __launch_bounds__(kThreads)
 compact_chunks_kernel(const ChunkDesc *__restrict__ chunks, const TensorChunks *__restrict__ spans, uint32_t n_tensors,
                       const uint8_t *__restrict__ mask, uint32_t tpc_shift, ChunkDesc *__restrict__ packed,
-                      uint64_t *__restrict__ n_slots_out) {
+                      uint64_t *__restrict__ n_slots_out, unsigned int *__restrict__ counters, uint32_t n_counters) {
   __shared__ uint64_t part[3][kThreads / 64];
   const uint32_t t = blockIdx.x, tid = threadIdx.x;
   uint64_t marked_before = 0, unmarked_before = 0, marked_total = 0;
@@ -207,6 +208,7 @@ compact_chunks_kernel(const ChunkDesc *__restrict__ chunks, const TensorChunks *
   empty.len = 0; empty.tensor = t; empty.vec_ok = 0; empty.elem0 = 0; empty.pad = 0;
   for (uint32_t k = tid; k < sp.count; k += kThreads) packed[dst + k] = marked ? chunks[sp.first + k] : empty;
   if (t == 0 && tid == 0) *n_slots_out = sum[2] << tpc_shift;
+  if (t == 0 && tid < n_counters) counters[tid * 32u] = 0;       // the tile counters of opt_queue_kernel, 128 bytes apart
 }
 
 }  // namespace swift

@@ -66,6 +66,15 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #ifndef SWIFT_DEFAULT_DMASK_WGS_PER_CU
 #define SWIFT_DEFAULT_DMASK_WGS_PER_CU 16384
 #endif
+#ifndef SWIFT_DMASK_QUEUE
+#define SWIFT_DMASK_QUEUE 1             // device-mask launches: 1 = resident wavefronts drawing tiles from counters, 0 = capped strided grid
+#endif
+#ifndef SWIFT_DMASK_COUNTERS
+#define SWIFT_DMASK_COUNTERS 64         // tile counters of the queue mode (a power of two, at most 256): 32 and 128 are slower
+#endif
+#ifndef SWIFT_DMASK_QUEUE_WAVES_PER_CU
+#define SWIFT_DMASK_QUEUE_WAVES_PER_CU 10 // resident wavefronts per CU in queue mode
+#endif
 #ifndef SWIFT_COPY_U
 #define SWIFT_COPY_U 1                  // copy kernel: 16-byte vectors per lane
 #endif
@@ -295,10 +304,15 @@ __device__ __forceinline__ void process_scalar(Op &op, const ChunkDesc &d, uint3
   if constexpr (Op::kStoreV) st<false>(d.v + e, ve);
 }
 
+// A hook lets a kernel slip one more memory request in behind a tile's loads, while they are in flight.
+struct NoHook {
+  __device__ __forceinline__ void after_loads() {}
+};
+
 // One tile: U*BLOCK 16-byte vectors (U*BLOCK*4 elements) of one chunk, starting at element
 // ti * U*BLOCK*4 of the chunk (the caller has checked that this is inside the chunk).
-template <typename Op, bool BF16G, int U, int BLOCK>
-__device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_t ti, uint32_t tid) {
+template <typename Op, bool BF16G, int U, int BLOCK, typename Hook = NoHook>
+__device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_t ti, uint32_t tid, Hook hook = Hook()) {
   constexpr bool HASV = Op::kHasV;
   constexpr uint32_t TILE4 = U * BLOCK;                          // vectors per tile
   const uint32_t len = d.len;
@@ -320,6 +334,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
         mr[u] = buf_ld4(rm, j * 16u);
         vr[u] = HASV ? buf_ld4(rv, j * 16u) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
+      hook.after_loads();
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t j = j0 + u * BLOCK + tid;
@@ -330,6 +345,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
         if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr[u]);
       }
     } else {                                                     // ragged end of a tensor
+      hook.after_loads();
       for (uint32_t j = j0 + tid; j < n4; j += BLOCK) {
         f32x4 xr = buf_ld4(rx, j * 16u), mr = buf_ld4(rm, j * 16u);
         f32x4 gr = Op::kLoadG ? load_grad4<BF16G>(rg, j) : f32x4{0.f, 0.f, 0.f, 0.f};
@@ -344,6 +360,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
       if (e < len) process_scalar<Op, BF16G>(op, d, e);          // (they start inside this tile)
     }
   } else {                                                       // unaligned tensor: 4-byte accesses
+    hook.after_loads();
     const uint32_t e0 = ti * (TILE4 * 4u);
     const uint32_t e1 = (e0 + TILE4 * 4u < len) ? e0 + TILE4 * 4u : len;
     for (uint32_t e = e0 + tid; e < e1; e += BLOCK) process_scalar<Op, BF16G>(op, d, e);
@@ -410,6 +427,52 @@ opt_packed_kernel(const ChunkDesc *__restrict__ chunks, const uint64_t *__restri
                   const OptConsts c) {
   typedef const __attribute__((address_space(4))) uint64_t *const_u64_ptr;   // uniform address: scalar load
   opt_tiles<KIND, UNDO, BF16G, XB, U, BLOCK, true>(chunks, *(const_u64_ptr)n_slots_dev, tpc_shift, c);
+}
+
+// The packed table again, but with a fixed grid of resident wavefronts that ask for their tiles: the
+// wavefronts of counter c (blockIdx mod n_counters) draw j = 0, 1, 2, ... from it and take slot
+// j * n_counters + c, so slots are handed out in address order, as the dispatcher does for one tile
+// per workgroup, and a launch costs time in proportion to the marked tiles only -- no workgroup is
+// dispatched for nothing, whatever the mask's density.  The request for the next index goes out
+// behind the current tile's loads and comes back while the tile is processed.  Every wavefront ends:
+// the counters only grow, and a wavefront leaves as soon as its slot is at or beyond the count.
+// counters: one 32-bit counter per 128 bytes, zero when the kernel starts (compact_chunks_kernel clears them).
+struct NextTile {
+  unsigned int *counter;
+  uint32_t *next;
+  __device__ __forceinline__ void after_loads() {
+    if (threadIdx.x == 0) *next = atomicAdd(counter, 1u);
+  }
+};
+
+template <int KIND, bool UNDO, bool BF16G, bool XB, int U, int BLOCK>
+__global__ void __launch_bounds__(BLOCK)
+opt_queue_kernel(const ChunkDesc *__restrict__ chunks, const uint64_t *__restrict__ n_slots_dev, uint32_t tpc_shift,
+                 const OptConsts c, unsigned int *__restrict__ counters, uint32_t log2_counters) {
+  typedef const __attribute__((address_space(4))) uint64_t *const_u64_ptr;
+  constexpr uint32_t TILE = U * BLOCK * 4u;
+  const uint32_t lane_c = blockIdx.x & ((1u << log2_counters) - 1u);
+  unsigned int *ctr = counters + lane_c * 32u;
+  const uint64_t end = *(const_u64_ptr)n_slots_dev;
+  uint32_t j = 0;
+  if (threadIdx.x == 0) j = atomicAdd(ctr, 1u);
+  j = (uint32_t)__builtin_amdgcn_readfirstlane((int)j);
+  OptOp<KIND, UNDO, XB> op{c};
+  for (;;) {
+    const uint64_t w = ((uint64_t)j << log2_counters) + lane_c;
+    if (w >= end) break;
+    const ChunkDesc d = fetch_desc(chunks + (w >> tpc_shift));
+    const uint32_t ti = (uint32_t)w & ((1u << tpc_shift) - 1u);
+    uint32_t nxt = 0;
+    NextTile hook{ctr, &nxt};
+    if (ti * TILE < d.len) process_tile<OptOp<KIND, UNDO, XB>, BF16G, U, BLOCK, NextTile>(op, d, ti, threadIdx.x, hook);
+    else hook.after_loads();
+    // The wavefront lets its stores drain before it takes its next tile, as a retiring workgroup would before its
+    // slot is reused (6.35 against 6.04 TB/s without); by then the next index has arrived as well.  Fetching the next
+    // tile's table entry one tile ahead (two indices in flight) was measured too and is slower (6.08).
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    j = (uint32_t)__builtin_amdgcn_readfirstlane((int)nxt);
+  }
 }
 
 // Plain copy with the same launch shape (one tile of U*BLOCK 16-byte vectors per workgroup): the
