@@ -1,5 +1,7 @@
 """Every element of the two large configurations against the fp64 oracle.
 
+(SGD with momentum on the 1.62 B list and Adam with coupled decay on the 1.56 B list get a full step and
+a full undo the same way, at the end of this file.)
 The 1.56 B-parameter list (bf16 gradients) and the 6.74 B-parameter list are stepped and undone by ONE
 library call each, in the launch configuration the benchmark times (same binding calls, default launch
 shape, state in the benchmark's default layout), and then ALL outputs -- theta, m and v of every tensor,
@@ -48,37 +50,41 @@ def synth():
 class Flow:
     """One workload's state on the device, its pre-call copy, and the streaming comparison."""
 
-    def __init__(self, B, synth, name):
+    def __init__(self, B, synth, name, variant=None):
         self.B, self.synth = B, synth
         w = synth.workloads()[name]
+        if variant is not None:                                  # the same shapes and values under another optimizer
+            w = synth.Workload(**{**w.__dict__, **variant})
         self.w = w
+        self.has_v = w.kind != "sgdm"
         self.sizes = [synth.numel(s) for s in w.shapes]
         self.n_t = len(self.sizes)
         self.N = sum(self.sizes)
         self.off = np.concatenate([[0], np.cumsum(self.sizes)]).astype(np.int64)
         self.s = synth.make_state(w, "cuda")                     # the benchmark's default layout
-        self.snap = [torch.empty(self.N, dtype=torch.float32, device="cuda") for _ in range(3)]
+        self.ns = 3 if self.has_v else 2                         # state streams: theta, m (, v)
+        self.snap = [torch.empty(self.N, dtype=torch.float32, device="cuda") for _ in range(self.ns)]
         self.hp = binding_hparams(B, w.kind, w.hyper, w.grad_bf16)
         self.oh = oracle_hyper(w.kind, w.hyper)
-        self.tl = B.TensorList(self.s.theta, self.s.grad, self.s.m, self.s.v)
+        self.tl = B.TensorList(self.s.theta, self.s.grad, self.s.m, self.s.v if self.has_v else None)
         frac = w.masked_fraction or 0.5
         self.mask = synth.tensor_mask(synth.Workload(**{**w.__dict__, "masked_fraction": frac}), self.n_t)
         gwords = [g.view(torch.int32) if g.dtype == torch.bfloat16 else g for g in self.s.grad]
         self.gbufs = B.BufferList(gwords)
-        self.sbufs = B.BufferList(self.s.theta + self.s.m + self.s.v)
+        self.sbufs = B.BufferList(sum(self.streams(), []))
         self.g_digest = digests_np(B.swift_state_digest(self.gbufs, 0)).copy()
         self.copy_stream = torch.cuda.Stream()
         gdt = torch.int16 if w.grad_bf16 else torch.float32
         mk = lambda dt: torch.empty(SLICE, dtype=dt, pin_memory=True)
-        self.pin = [dict(pre=[mk(torch.float32) for _ in range(3)], g=mk(gdt), post=[mk(torch.float32) for _ in range(3)])
-                    for _ in range(2)]
+        self.pin = [dict(pre=[mk(torch.float32) for _ in range(self.ns)], g=mk(gdt),
+                         post=[mk(torch.float32) for _ in range(self.ns)]) for _ in range(2)]
         self.pool = cf.ThreadPoolExecutor(WORKERS)
         self.done = []                                            # stages already run
         self.worst = 0.0
         self.snapshot()
 
     def streams(self):
-        return [self.s.theta, self.s.m, self.s.v]
+        return [self.s.theta, self.s.m] + ([self.s.v] if self.has_v else [])
 
     def snapshot(self):
         for k, ts in enumerate(self.streams()):
@@ -137,7 +143,7 @@ class Flow:
         a, b, marked = job
         n = b - a
         with torch.cuda.stream(self.copy_stream):
-            for k in range(3):
+            for k in range(self.ns):
                 pin["pre"][k][:n].copy_(self.snap[k][a:b], non_blocking=True)
             pos = 0
             for (i, lo, hi) in self.pieces(a, b):
@@ -159,7 +165,7 @@ class Flow:
         pre = [p[:n].numpy() for p in pin["pre"]]
         post = [p[:n].numpy() for p in pin["post"]]
         if not marked:
-            for k in range(3):
+            for k in range(self.ns):
                 assert np.array_equal(pre[k].view(np.uint32), post[k].view(np.uint32)), \
                     f"{what}: an unmarked tensor changed in elements [{a}, {b})"
             return 0.0
@@ -172,15 +178,21 @@ class Flow:
             lo, hi = bounds[k], bounds[k + 1]
             if lo == hi:
                 return 0.0
-            x, gg, m, v = pre[0][lo:hi], g[lo:hi], pre[1][lo:hi], pre[2][lo:hi]
+            x, gg, m = pre[0][lo:hi], g[lo:hi], pre[1][lo:hi]
+            v = pre[2][lo:hi] if self.has_v else None
             rx, rm, rv = fn(self.oh, x, gg, m, v)
             sc = max(float(np.abs(x).max()), float(np.abs(oracle.widen(gg)).max()), float(np.abs(m).max()),
-                     float(np.abs(v).max()))
+                     float(np.abs(v).max()) if self.has_v else 0.0)
             tag = f"{what} elements [{a + lo}, {a + hi})"
-            worst = assert_parity(post[0][lo:hi], rx, tag + " theta", sc)
+            assert_parity(post[0][lo:hi], rx, tag + " theta", sc)
             assert_parity(post[1][lo:hi], rm, tag + " m", sc)
-            assert_parity(post[2][lo:hi], rv, tag + " v", sc * max(sc, 1.0))
-            return worst
+            if self.has_v:
+                assert_parity(post[2][lo:hi], rv, tag + " v", sc * max(sc, 1.0))
+            # what is reported: the largest error in units of the tolerance max(1e-5 |oracle|, 1e-8)
+            used = 0.0
+            for q, r in ((post[0][lo:hi], rx), (post[1][lo:hi], rm)) + (((post[2][lo:hi], rv),) if self.has_v else ()):
+                used = max(used, float(np.max(np.abs(q.astype(np.float64) - r) / np.maximum(1e-5 * np.abs(r), 1e-8))))
+            return used
         return max(self.pool.map(part, range(WORKERS)))
 
     def run(self, stage, check=True):
@@ -217,9 +229,21 @@ class Flow:
 _current = {}
 
 
+# Other optimizers on the same shapes: Adam with coupled decay (App. A "Adam" / "Undo Adam") on the 1.56 B list.
+VARIANTS = {
+    "gpt2_xl_adam_l2_bf16g": ("gpt2_xl_adamw_bf16g",
+                              dict(name="gpt2_xl_adam_l2_bf16g", kind="adam",
+                                   hyper=dict(lr=1e-3, weight_decay=0.01, beta1=0.9, beta2=0.999, eps=1e-8, step=1000))),
+}
+
+
 def _flow(B, synth, name):
     """One large state at a time: switching workloads releases the previous one first."""
-    if _current.get("name") != name:
+    key = name
+    variant = None
+    if name in VARIANTS:
+        name, variant = VARIANTS[name]
+    if _current.get("name") != key:
         old = _current.pop("flow", None)
         _current.clear()
         if old is not None:
@@ -227,12 +251,12 @@ def _flow(B, synth, name):
             del old
         torch.cuda.empty_cache()
         w = synth.workloads()[name]
-        need = w.n_params * ((2 if w.grad_bf16 else 4) + 12 + 12) * 1.04 + 4e9
+        need = w.n_params * ((2 if w.grad_bf16 else 4) + 12 + 12) * 1.04 + 4e9         # state, its copy, padding
         free, _ = torch.cuda.mem_get_info()
         if free < need:
             pytest.skip(f"needs about {need / 1e9:.0f} GB of free device memory")
-        _current["flow"] = Flow(B, synth, name)
-        _current["name"] = name
+        _current["flow"] = Flow(B, synth, name, variant)
+        _current["name"] = key
     return _current["flow"]
 
 
@@ -257,4 +281,20 @@ def test_every_element_against_the_oracle(B, synth, name, stage, capsys):
     dt = time.perf_counter() - t0
     with capsys.disabled():
         print(f"\n[full coverage] {name} {stage}: {compared:,} elements x (theta, m, v) compared in {dt:.1f} s, "
-              f"largest relative error so far {flow.worst:.2e}", flush=True)
+              f"largest error so far {flow.worst:.3f} of the tolerance", flush=True)
+
+
+@pytest.mark.parametrize("stage", ["full_step", "full_undo"])
+@pytest.mark.parametrize("name", ["vit_128_32_sgdm", "gpt2_xl_adam_l2_bf16g"])
+def test_every_element_other_optimizers(B, synth, name, stage, capsys):
+    """SGD with momentum (Alg. 1 / Alg. 2) on the 1.62 B-parameter list and Adam with coupled decay on the 1.56 B
+    list with bf16 gradients: one full step and one full undo each, every element against the oracle."""
+    flow = _flow(B, synth, name)
+    if stage == "full_undo" and "full_step" not in flow.done:
+        flow.run("full_step", check=False)
+    t0 = time.perf_counter()
+    compared = flow.run(stage)
+    dt = time.perf_counter() - t0
+    with capsys.disabled():
+        print(f"\n[full coverage] {name} {stage}: {compared:,} elements x {flow.ns} state streams compared in {dt:.1f} s, "
+              f"largest error so far {flow.worst:.3f} of the tolerance", flush=True)
