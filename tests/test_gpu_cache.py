@@ -106,3 +106,95 @@ def test_reallocated_tensors_are_checked_again(B):
     B.swift_opt_undo(tl, hp)                           # same allocation: same tables
     assert B.swift_cache_stats()[0] == n_before + 1
     torch.cuda.synchronize()
+
+
+def test_a_list_whose_memory_was_freed_is_validated_again(B):
+    """The caller frees its tensors (the memory goes back to the runtime, which may hand the address out again for a
+    smaller buffer): a later call with the old pointers and sizes must be refused by the pointer checks -- the cached
+    tables are dropped and rebuilt, which validates again -- not run on memory that is gone."""
+    hp = binding_hparams(B, "adamw", HPD)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    n = 1 << 22
+    big = torch.zeros(4 * n, dtype=torch.float32, device="cuda")            # 64 MiB: an allocation of its own
+    base = big.data_ptr()
+    parts = [[big[k * n:(k + 1) * n]] for k in range(4)]
+    tl = B.TensorList(*parts)
+    B.swift_opt_step(tl, hp)
+    B.swift_opt_undo(tl, hp)
+    torch.cuda.synchronize()
+    n_lists = B.swift_cache_stats()[0]
+    del parts, big
+    tl._keep = None                                                          # the marshalled pointer arrays stay
+    torch.cuda.empty_cache()                                                 # the 64 MiB go back to the runtime
+    small = torch.zeros(n, dtype=torch.float32, device="cuda")              # 16 MiB, possibly at the freed address
+    with pytest.raises(B.SwiftError) as e:
+        B.swift_opt_step(tl, hp)         # same pointers, same sizes: unknown to the runtime now, or beyond `small`
+    assert e.value.code == B.SWIFT_EINVAL
+    assert ("run past the end" in e.value.message) if small.data_ptr() == base else True
+    assert B.swift_cache_stats()[0] == n_lists - 1                           # the stale tables are gone
+    torch.cuda.synchronize()
+    assert float(small.abs().max()) == 0.0                                   # nothing ran
+
+
+def test_concurrent_callers(B):
+    """Four host threads step and undo their own lists (and digest a shared one) at the same time: results equal
+    a serial run, the cache ends up with one entry per distinct list."""
+    import threading
+    hp = binding_hparams(B, "adamw", HPD)
+    B.swift_cache_trim(0)
+    base = B.swift_cache_stats()[0]
+    flats, lists = [], []
+    for t in range(4):
+        f, ls = _lists(B, 8, 3000 + 17 * t, seed=10 + t)
+        flats.append(f)
+        lists.append(ls)
+    ref = [[x.clone() for x in f] for f in flats]
+    ref_lists = []
+    for t in range(4):
+        numel = 3000 + 17 * t
+        cut = lambda f, i: [f[i * numel:(i + 1) * numel]]
+        ref_lists.append([B.TensorList(cut(ref[t][0], i), cut(ref[t][1], i), cut(ref[t][2], i), cut(ref[t][3], i)) for i in range(8)])
+    shared = torch.arange(100000, dtype=torch.float32, device="cuda")
+    want = B.swift_state_digest([shared], 1 << 12)
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(t):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(20):
+                    for tl in lists[t]:
+                        B.swift_opt_step(tl, hp, stream=stream)
+                    got = B.swift_state_digest([shared], 1 << 12, stream=stream)
+                    for tl in reversed(lists[t]):
+                        B.swift_opt_undo(tl, hp, stream=stream)
+                    for tl in lists[t]:
+                        B.swift_opt_step(tl, hp, stream=stream)
+                    stream.synchronize()
+                    if not torch.equal(got, want):
+                        errors.append(f"thread {t}: digest differs")
+        except Exception as exc:                                             # noqa: BLE001
+            errors.append(f"thread {t}: {exc!r}")
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    for t in range(4):                                                       # the same 20 rounds, serially
+        for rep in range(20):
+            for tl in ref_lists[t]:
+                B.swift_opt_step(tl, hp)
+            for tl in reversed(ref_lists[t]):
+                B.swift_opt_undo(tl, hp)
+            for tl in ref_lists[t]:
+                B.swift_opt_step(tl, hp)
+    torch.cuda.synchronize()
+    for t in range(4):
+        for a, b in zip(flats[t], ref[t]):
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    n_now = B.swift_cache_stats()[0]
+    assert n_now == base + 4 * 8 * 2 + 1                                    # 64 optimizer lists (two copies) + the digest list
