@@ -366,11 +366,9 @@ struct Tuning {
 
 Tuning opt_tuning(int kind, bool bf16, bool undo) {
   // Measured optima: the fewer bytes a wavefront moves (SGDM has 3 streams in and 2 out instead of
-  // 4 and 3; bf16 gradients halve one stream), the more wavefronts a compute unit wants; with bf16
-  // gradients the Adam-family undo wants two more than the step (GPT-2 list: 6.30 against 6.56 ms).
-  int waves;
-  if (kind == SWIFT_SGDM) waves = SWIFT_DEFAULT_WAVES_PER_CU_SGDM + (bf16 ? 1 : 0);
-  else waves = SWIFT_DEFAULT_WAVES_PER_CU + (bf16 ? (undo ? 3 : 1) : 0);
+  // 4 and 3; bf16 gradients halve one stream), the more wavefronts a compute unit wants.
+  (void)undo;      // step and undo want the same residency once every load of a tile is issued up front
+  const int waves = (kind == SWIFT_SGDM ? SWIFT_DEFAULT_WAVES_PER_CU_SGDM : SWIFT_DEFAULT_WAVES_PER_CU) + (bf16 ? 1 : 0);
   const Knobs k = knobs();
   return Tuning{(int)k.tile_u, (int)k.tile_block, k.waves_per_cu == kUnset ? waves : (int)k.waves_per_cu};
 }
