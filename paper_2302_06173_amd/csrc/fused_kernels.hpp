@@ -25,11 +25,14 @@ template <int KIND, bool UNDO, bool XB>
 struct OptDigestOp {       // step or undo of one element + digest contributions of its new words
   static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
   static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = XB;
+  static constexpr bool kPost = true;      // the words are mixed after their stores have been issued
   const OptConsts &c;
   uint32_t base;           // index of the chunk's first element inside its tensor, plus the mixer's K1.hi
   uint64_t dx = 0, dm = 0, dv = 0;
-  __device__ __forceinline__ void elem(uint32_t i, float &x, float g, float &m, float &v) {
+  __device__ __forceinline__ void elem(uint32_t, float &x, float g, float &m, float &v) {
     update_elem<KIND, UNDO>(x, g, m, v, c);
+  }
+  __device__ __forceinline__ void post(uint32_t i, float x, float m, float v) {
     const uint32_t idx = base + i;
     dx += digest_mix_pre(idx, __float_as_uint(x));
     dm += digest_mix_pre(idx, __float_as_uint(m));

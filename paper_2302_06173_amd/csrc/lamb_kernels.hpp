@@ -48,6 +48,7 @@ __device__ __forceinline__ double wave_sum_f64(double s) {
 // Pass 1 of the step: the moment recurrences (written back) and the running sums for the norms.
 struct LambMomentsOp {
   static constexpr bool kLoadG = true, kHasV = true, kStoreX = false, kStoreM = true, kStoreV = true, kStoreXB = false;
+  static constexpr bool kPost = false;
   const OptConsts &c;
   double sx = 0.0, su = 0.0;
   __device__ __forceinline__ void elem(uint32_t, float &xf, float gf, float &mf, float &vf) {
@@ -67,6 +68,7 @@ struct LambMomentsOp {
 template <bool XB>
 struct LambApplyOp {
   static constexpr bool kLoadG = false, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false, kStoreXB = XB;
+  static constexpr bool kPost = false;
   const OptConsts &c;
   double eta_q;
   __device__ __forceinline__ void elem(uint32_t, float &xf, float, float &mf, float &vf) {

@@ -49,7 +49,7 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #define SWIFT_FUSED_U 1                 // step/undo fused with the digest: vectors per lane
 #endif
 #ifndef SWIFT_FUSED_WAVES_PER_CU
-#define SWIFT_FUSED_WAVES_PER_CU 24     // step/undo fused with the digest
+#define SWIFT_FUSED_WAVES_PER_CU 20     // step/undo fused with the digest
 #endif
 #ifndef SWIFT_LAMB_U1
 #define SWIFT_LAMB_U1 1                 // LAMB pass 1: vectors per lane (tile = U * 256 elements, one partial sum pair per tile)
@@ -239,10 +239,14 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
 //   kStoreXB               the bfloat16 copy of the new theta is written too
 //   elem(i, x, g, m, v)    the arithmetic of element i of the chunk (may also accumulate into
 //                          members of the op)
+//   kPost, post(i, x, m, v)  if kPost: called for element i with the values that were stored, AFTER the
+//                          stores of its vector have been issued (work that only reads the results runs
+//                          while the stores are on their way)
 template <int KIND, bool UNDO, bool XB = false>
 struct OptOp {             // optimizer step or undo of one element
   static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
   static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = XB;
+  static constexpr bool kPost = false;
   const OptConsts &c;
   __device__ __forceinline__ void elem(uint32_t, float &x, float g, float &m, float &v) {
     update_elem<KIND, UNDO>(x, g, m, v, c);
@@ -259,6 +263,12 @@ __device__ __forceinline__ void update_vec4(Op &op, uint32_t j, f32x4 &x, const 
     m[k] = me;
     if constexpr (Op::kHasV) v[k] = ve;
   }
+}
+
+template <typename Op>
+__device__ __forceinline__ void post_vec4(Op &op, uint32_t j, const f32x4 &x, const f32x4 &m, const f32x4 &v) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) op.post(4u * j + k, x[k], m[k], Op::kHasV ? v[k] : 0.f);
 }
 
 // The bfloat16 copy of vector j (4 consecutive elements): 8 bytes.
@@ -302,6 +312,7 @@ __device__ __forceinline__ void process_scalar(Op &op, const ChunkDesc &d, uint3
   if constexpr (Op::kStoreXB) st<false>(d.xb + e, (uint16_t)f32_to_bf16_bits(xe));
   if constexpr (Op::kStoreM) st<false>(d.m + e, me);
   if constexpr (Op::kStoreV) st<false>(d.v + e, ve);
+  if constexpr (Op::kPost) op.post(e, xe, me, ve);
 }
 
 // A hook lets a kernel slip one more memory request in behind a tile's loads, while they are in flight.
@@ -348,6 +359,10 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
         if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr[u]);
         if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr[u]);
       }
+      if constexpr (Op::kPost) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) post_vec4(op, j0 + u * BLOCK + tid, xr[u], mr[u], vr[u]);
+      }
     } else {                                                     // ragged end of a tensor
       hook.after_loads();
       for (uint32_t j = j0 + tid; j < n4; j += BLOCK) {
@@ -359,6 +374,7 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
         if constexpr (Op::kStoreXB) buf_st_bf16x4(rxb, j, xr);
         if constexpr (Op::kStoreM) buf_st4(rm, j * 16u, mr);
         if constexpr (Op::kStoreV) buf_st4(rv, j * 16u, vr);
+        if constexpr (Op::kPost) post_vec4(op, j, xr, mr, vr);
       }
       const uint32_t e = (n4 << 2) + tid;                        // last numel % 4 elements
       if (e < len) process_scalar<Op, BF16G>(op, d, e);          // (they start inside this tile)
