@@ -911,11 +911,8 @@ int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, cons
   if (l->n > kNoallocMaxTensors)
     return fail(SWIFT_EINVAL, "swift_opt_undo_dmask_noalloc takes at most %lld tensors per call (got %lld)",
                 (long long)kNoallocMaxTensors, (long long)l->n);
-  uint64_t total = 0, longest = 0;
-  for (int64_t i = 0; i < l->n; ++i) {
-    total += (uint64_t)l->numel[i];
-    longest = std::max<uint64_t>(longest, (uint64_t)l->numel[i]);
-  }
+  uint64_t total = 0;
+  for (int64_t i = 0; i < l->n; ++i) total += (uint64_t)l->numel[i];
   // the shortest chunk length (a power of two, at least the small-list length) whose table fits
   uint32_t ce = 16384;
   auto chunks_at = [&](uint64_t len) {
@@ -927,7 +924,6 @@ int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, cons
   if (chunks_at(ce) > (uint64_t)kNoallocMaxChunks)
     return fail(SWIFT_EINVAL, "swift_opt_undo_dmask_noalloc: %llu elements in %lld tensors need more than %lld chunks of "
                 "%u elements; split the list", (unsigned long long)total, (long long)l->n, (long long)kNoallocMaxChunks, ce);
-  (void)longest;
   int dev = -1;
   SWIFT_HIP(hipGetDevice(&dev));
   DeviceInfo info;
@@ -1399,8 +1395,7 @@ int swift_opt_undo_dmask(const swift_tensor_list *list, const swift_hparams *hp,
 
 int swift_opt_undo_dmask_noalloc(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *device_mask,
                                  void *hip_stream) {
-  // no guarded(): nothing on this path allocates, so nothing can throw
-  return noalloc_undo_dmask(list, hp, device_mask, hip_stream);
+  return guarded([&] { return noalloc_undo_dmask(list, hp, device_mask, hip_stream); });   // (an error message may allocate host memory)
 }
 
 int swift_opt_step_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
