@@ -160,6 +160,10 @@ struct Plan {
   void *fused_slots = nullptr;
   void *fused_tiles = nullptr;
   uint32_t fused_tile_elems = 0;
+  // digest plans whose shards span several chunks: per-output spans and per-chunk sums (built with the plan)
+  void *digest_spans = nullptr;
+  void *digest_partial = nullptr;
+  bool digest_has_empty = false;   // some output belongs to an empty buffer (its digest, 0, is written by a fill)
   // device-mask calls only, created on first use (guarded by lamb_mu): [tensor spans | packed chunk table | slot count]
   void *packed_mem = nullptr;
   size_t packed_table_off = 0, packed_count_off = 0;
@@ -175,6 +179,8 @@ struct Plan {
       if (fused_spans) (void)hipFree(fused_spans);
       if (fused_slots) (void)hipFree(fused_slots);
       if (fused_tiles) (void)hipFree(fused_tiles);
+      if (digest_spans) (void)hipFree(digest_spans);
+      if (digest_partial) (void)hipFree(digest_partial);
       if (packed_mem) (void)hipFree(packed_mem);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
     }
@@ -1258,8 +1264,7 @@ int64_t digest_count(int64_t n_buf, const int64_t *numel, int64_t shard_elems, b
   return total;
 }
 
-// Digest chunks: one workgroup and one 64-bit atomic per chunk.  Long chunks mean fewer atomics on
-// one address (whole-tensor shards of large tensors), but the launch still needs about sixteen
+// Digest chunks: one workgroup and one 64-bit partial sum per chunk.  The launch needs about sixteen
 // workgroups per compute unit to fill the chip, so the length follows the total size.
 uint32_t digest_chunk_elems(uint64_t total, int64_t shard_elems, int cus) {
   const uint32_t tile = 4u * kThreads * 4;                     // chunk lengths are multiples of four rounds of the kernel
@@ -1319,16 +1324,23 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   const uint64_t ce = plan->chunk_elems;
   std::vector<ChunkRef> chunks;
   chunks.reserve((size_t)(total / ce) + (size_t)n_out);
+  std::vector<DigestSpan> spans((size_t)n_out, DigestSpan{0, 0});
+  bool single = true;                                       // every shard is one chunk
   for (int64_t i = 0; i < n_buf; ++i) {
     const uint64_t n = (uint64_t)numel[i];
-    if (n == 0) continue;
+    if (n == 0) {
+      if (shard_elems == 0) plan->digest_has_empty = true;  // one output, no chunk
+      continue;
+    }
     const uint64_t S = shard_elems ? (uint64_t)shard_elems : n;
     const uint64_t cps = (S + ce - 1) / ce;                 // chunk numbers per full shard
     const uint64_t n_shards = (n + S - 1) / S;
     if (cps * n_shards > 0xffffffffull) return fail(SWIFT_EINVAL, "digest: buffer %lld needs too many chunks", (long long)i);
+    if (cps > 1) single = false;
     for (uint64_t s = 0; s < n_shards; ++s) {
       const uint64_t shard_len = std::min<uint64_t>(S, n - s * S);
       const uint64_t nc = (shard_len + ce - 1) / ce;
+      spans[(size_t)(descs[(size_t)i].first_out + s)] = DigestSpan{chunks.size(), nc};
       for (uint64_t k = 0; k < nc; ++k) chunks.push_back({(uint32_t)i, (uint32_t)(s * cps + k)});
     }
   }
@@ -1336,6 +1348,13 @@ int build_digest_plan(int64_t n_buf, const void *const *buf, const int64_t *nume
   int rc = upload_plan(*plan, descs.data(), descs.size() * sizeof(DigestDesc), chunks.data(), chunks.size(),
                        sizeof(ChunkRef));
   if (rc) return rc;
+  if (!single) {                                            // chunk sums are gathered per shard by a second kernel
+    const size_t span_bytes = spans.size() * sizeof(DigestSpan), part_bytes = chunks.size() * sizeof(uint64_t);
+    SWIFT_HIP(hipMalloc(&plan->digest_spans, span_bytes));
+    SWIFT_HIP(hipMemcpy(plan->digest_spans, spans.data(), span_bytes, hipMemcpyHostToDevice));
+    SWIFT_HIP(hipMalloc(&plan->digest_partial, part_bytes));
+    plan->dev_bytes += span_bytes + part_bytes;
+  }
   for (int64_t i = 0; i < n_buf && !plan->probe_ptr; ++i)
     if (numel[i] > 0) set_probe(*plan, buf[i]);
   keep_plan(plan);
@@ -1439,19 +1458,37 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
     std::shared_ptr<Plan> plan;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if ((rc = build_digest_plan(n_buf, buf, numel, shard_elems, dev, info.cus, stream, &plan))) return rc;
-    // The output is cleared by a kernel (not a memset node) so that the call can be captured in a graph.
-    const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
-    hipLaunchKernelGGL(fill_u64_kernel, dim3(fill_grid), dim3(kThreads), 0, stream, out_device, (uint64_t)n_out,
-                       (uint64_t)0);
-    SWIFT_HIP(hipGetLastError());
-    if (plan->n_chunks == 0) return SWIFT_OK;
-    const uint32_t grid = plan->n_chunks;                        // one workgroup per chunk
-    const Tuning dtune{1, kThreads, (int)knobs().digest_waves_per_cu};
-    hipLaunchKernelGGL(digest_kernel, dim3(grid), dim3(kThreads), lds_cap_bytes(info, dtune), stream, static_cast<const DigestDesc *>(plan->descs()),
-                       static_cast<const ChunkRef *>(plan->chunks()), plan->n_chunks, plan->chunk_elems,
-                       (uint64_t)shard_elems,
-                       reinterpret_cast<unsigned long long *>(out_device));
-    SWIFT_HIP(hipGetLastError());
+    uint64_t *out = out_device;
+    uint64_t *partial = static_cast<uint64_t *>(plan->digest_partial);
+    // Shards of several chunks: chunk sums, then one wavefront per shard adds them up and writes every output
+    // (an empty buffer's too).  Single-chunk shards: each output is written by its one chunk; only the digests
+    // of empty buffers (0) need a fill, by a kernel, not a memset node, so that the call can be captured.
+    if (!partial && plan->digest_has_empty) {
+      const uint32_t fill_grid = (uint32_t)std::min<uint64_t>(((uint64_t)n_out + kThreads - 1) / kThreads, 1024);
+      hipLaunchKernelGGL(fill_u64_kernel, dim3(fill_grid), dim3(kThreads), 0, stream, out, (uint64_t)n_out, (uint64_t)0);
+      SWIFT_HIP(hipGetLastError());
+    }
+    if (plan->n_chunks) {
+      const uint32_t grid = plan->n_chunks;                      // one workgroup per chunk
+      const Tuning dtune{1, kThreads, (int)knobs().digest_waves_per_cu};
+      hipLaunchKernelGGL(digest_kernel, dim3(grid), dim3(kThreads), lds_cap_bytes(info, dtune), stream,
+                         static_cast<const DigestDesc *>(plan->descs()), static_cast<const ChunkRef *>(plan->chunks()),
+                         plan->n_chunks, plan->chunk_elems, (uint64_t)shard_elems, partial, out);
+      SWIFT_HIP(hipGetLastError());
+    }
+    if (partial) {
+      const DigestSpan *spans = static_cast<const DigestSpan *>(plan->digest_spans);
+      if ((uint64_t)plan->n_chunks >= 64ull * (uint64_t)n_out && (uint64_t)n_out <= 0x7fffffffull) {
+        hipLaunchKernelGGL(digest_reduce_kernel<true>, dim3((uint32_t)n_out), dim3(kThreads), 0, stream, spans,
+                           static_cast<const uint64_t *>(partial), (uint64_t)n_out, out);
+      } else {
+        const uint64_t per_block = kThreads / 64;
+        if (((uint64_t)n_out + per_block - 1) / per_block > 0x7fffffffull) return fail(SWIFT_EINVAL, "digest: too many outputs");
+        hipLaunchKernelGGL(digest_reduce_kernel<false>, dim3((uint32_t)(((uint64_t)n_out + per_block - 1) / per_block)),
+                           dim3(kThreads), 0, stream, spans, static_cast<const uint64_t *>(partial), (uint64_t)n_out, out);
+      }
+      SWIFT_HIP(hipGetLastError());
+    }
     return SWIFT_OK;
   });
 }

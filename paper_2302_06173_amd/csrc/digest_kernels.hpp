@@ -3,7 +3,7 @@
 // The digest of a shard is the modulo-2^64 sum of a bijectively mixed (index, word) pair per
 // 32-bit word, so partial sums can be combined in any order: lanes accumulate privately, a
 // wavefront combines its 64 lanes with DPP row operations and cross-row lane reads, the four
-// wavefronts of a workgroup meet in LDS, and one 64-bit atomic add per chunk lands in the output.
+// wavefronts of a workgroup meet in LDS, and a second small kernel adds the chunk sums of a shard.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -90,10 +90,13 @@ __global__ void __launch_bounds__(kThreads) fill_u64_kernel(uint64_t *p, uint64_
 // Chunk numbering inside a buffer: a full shard spans cps = ceil(S / chunk_elems) chunk numbers,
 // chunk = shard * cps + k covers words [shard*S + k*CE, ...) of the buffer, i.e. shard-relative
 // indices [k*CE, min(k*CE + CE, shard length)).  S = shard_elems, or numel when shard_elems = 0.
-// `out` must be zero when the kernel starts.
+// The chunk's sum goes to partial[ci] if `partial` is given (digest_reduce_kernel then adds the
+// chunks of each shard; atomic adds of hundreds of chunks into one output serialise and cost a
+// mid-size buffer most of its time), else straight to out[shard]: the host passes no `partial`
+// only when every shard is a single chunk.
 __global__ void __launch_bounds__(kThreads)
 digest_kernel(const DigestDesc *__restrict__ descs, const ChunkRef *__restrict__ chunks, uint32_t n_chunks,
-              uint32_t chunk_elems, uint64_t shard_elems, unsigned long long *__restrict__ out) {
+              uint32_t chunk_elems, uint64_t shard_elems, uint64_t *__restrict__ partial, uint64_t *__restrict__ out) {
   constexpr bool NT = SWIFT_NT != 0;
   __shared__ uint64_t wave_part[kThreads / 64];
   const uint32_t tid = threadIdx.x;
@@ -139,9 +142,52 @@ digest_kernel(const DigestDesc *__restrict__ descs, const ChunkRef *__restrict__
       uint64_t t = 0;
 #pragma unroll
       for (int wv = 0; wv < kThreads / 64; ++wv) t += wave_part[wv];
-      atomicAdd(out + d.first_out + shard, (unsigned long long)t);
+      if (partial) partial[ci] = t;
+      else out[d.first_out + shard] = t;
     }
     __syncthreads();                                             // wave_part is reused by the next chunk
+  }
+}
+
+// Where the chunk sums of one output (one shard) sit in the partial array: consecutive entries.
+struct DigestSpan {
+  uint64_t first;
+  uint64_t count;            // 0: an empty buffer digested as one shard; its digest is 0
+};
+
+// out[o] = sum of the chunk sums of output o.  WG = false: one wavefront per output (many outputs of a few
+// chunks each); WG = true: one workgroup per output (few outputs of hundreds of chunks: the loads of one
+// wavefront alone would be a chain of memory latencies).  Four loads are in flight per lane.
+template <bool WG>
+__global__ void __launch_bounds__(kThreads)
+digest_reduce_kernel(const DigestSpan *__restrict__ spans, const uint64_t *__restrict__ partial, uint64_t n_out,
+                     uint64_t *__restrict__ out) {
+  constexpr uint32_t L = WG ? kThreads : 64;
+  const uint64_t o = WG ? (uint64_t)blockIdx.x : (uint64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (o >= n_out) return;                                        // whole wavefronts leave together; never taken if WG
+  const DigestSpan sp = spans[o];
+  const uint64_t *p = partial + sp.first;
+  uint64_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+  uint64_t k = WG ? threadIdx.x : (threadIdx.x & 63u);
+  for (; k + 3 * L < sp.count; k += 4 * L) {
+    a0 += p[k];
+    a1 += p[k + L];
+    a2 += p[k + 2 * L];
+    a3 += p[k + 3 * L];
+  }
+  for (; k < sp.count; k += L) a0 += p[k];
+  const uint64_t wsum = wave_sum_u64((a0 + a1) + (a2 + a3));
+  if constexpr (WG) {
+    __shared__ uint64_t wave_part[kThreads / 64];
+    if ((threadIdx.x & 63u) == 0) wave_part[threadIdx.x >> 6] = wsum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint64_t t = 0;
+      for (int wv = 0; wv < kThreads / 64; ++wv) t += wave_part[wv];
+      out[o] = t;
+    }
+  } else {
+    if ((threadIdx.x & 63u) == 0) out[o] = wsum;
   }
 }
 

@@ -425,6 +425,25 @@ def test_digest_bit_exact(B, shard):
     assert np.array_equal(digests_np(out), want)
 
 
+@pytest.mark.parametrize("sizes", [
+    [100, 0, 4096, 0, 1, 2049],              # every buffer is one chunk; the empty ones get their 0 from a fill
+    [0, 0],                                  # nothing but empty buffers
+    [(1 << 21) + 77, 0, 1 << 21, 3 << 19],   # hundreds of chunks per output: one workgroup adds each output's sums
+])
+def test_digest_whole_buffers_with_empty_ones(B, sizes):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(62)
+    bufs = [torch.empty(n, dtype=torch.float32, device="cuda").normal_(0, 1, generator=gen) for n in sizes]
+    out = torch.full((len(sizes),), -1, dtype=torch.int64, device="cuda")
+    want = oracle.digest_list([to_np(b) for b in bufs], 0)
+    for _ in range(2):                       # the second call finds the first one's values in out and in the scratch
+        B.swift_state_digest(bufs, 0, out=out)
+        torch.cuda.synchronize()
+        got = digests_np(out)
+        assert np.array_equal(got, want), np.nonzero(got != want)[0][:8]
+    assert all(want[i] == 0 for i, n in enumerate(sizes) if n == 0)
+
+
 def test_digest_detects_a_single_flipped_bit_and_drives_selective_undo(B, synth):
     # the flow of a failure in mid-update: digests at iteration t, a step that reaches only some
     # tensors, digests again, mask from the digests (on the device), undo exactly those tensors
