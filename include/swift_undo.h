@@ -247,8 +247,10 @@ int swift_mask_from_digests(int64_t n_tensors, int64_t n_groups, const uint64_t 
 /* Update tracker: the paper's own bookkeeping (Implementation, "Update-undo").  In data-parallel
  * training the update of a tensor is launched as soon as its gradient is final (after that tensor's
  * all-reduce), and the tensor is then marked as updated; after a failure the survivors let the kernels
- * already launched finish and undo exactly the marked tensors.  The tracker is host state plus one event
- * per tracked launch; ids refer to the positions of the tensors in the caller's full list.
+ * already launched finish and undo exactly the marked tensors.  The tracker is host state (the marks and the
+ * streams that carried this iteration's launches); ids refer to the positions of the tensors in the caller's
+ * full list.  A stream given to swift_tracker_step must stay alive until the iteration's swift_tracker_undo or
+ * swift_tracker_marks has returned or the next swift_tracker_begin.
  *   swift_tracker_create   n_tensors >= 0; *out receives the handle (HOST, owned by the library).
  *   swift_tracker_begin    starts iteration `step` (>= 1) and drops the marks of the previous one.
  *   swift_tracker_step     `group` is a sub-list of the full list, tensor_ids[k] (HOST, group->n entries)
@@ -257,12 +259,14 @@ int swift_mask_from_digests(int64_t n_tensors, int64_t n_groups, const uint64_t 
  *                          swift_opt_step(group, hp, NULL, stream) is enqueued and the ids are marked.
  *                          hp->step must equal the iteration in progress; an id already marked in this
  *                          iteration is an error (SWIFT_EINVAL) and nothing is enqueued.
- *   swift_tracker_marks    waits until every tracked launch of this iteration has finished, then copies
- *                          the marks (HOST, n_tensors bytes, 1 = updated).
- *   swift_tracker_undo     the same wait, then swift_opt_undo(list, hp, marks, stream) on the FULL list
- *                          (list->n must equal n_tensors) and the marks are cleared: the replica is back
- *                          at the start of the iteration.
- *   swift_tracker_destroy  waits for tracked launches, frees the handle (NULL is allowed).
+ *   swift_tracker_marks    waits (on the host) until the streams that carried this iteration's tracked
+ *                          launches have drained, then copies the marks (HOST, n_tensors bytes, 1 = updated).
+ *   swift_tracker_undo     enqueues swift_opt_undo(list, hp, marks, stream) on the FULL list (list->n must
+ *                          equal n_tensors) behind every tracked launch of the iteration: by stream order
+ *                          where they share `stream`, else through an event that `stream` waits for on the
+ *                          device.  The host does not wait.  The marks are cleared: once the stream has run,
+ *                          the replica is back at the start of the iteration.
+ *   swift_tracker_destroy  frees the handle (NULL is allowed); launches in flight are not affected.
  * One tracker serves one GPU and one training loop; its calls are serialised by an internal lock. */
 typedef struct swift_tracker swift_tracker;
 int swift_tracker_create(int64_t n_tensors, swift_tracker **out);

@@ -1372,19 +1372,35 @@ struct Tracker {
   int64_t step = 0;                    // iteration whose update is in progress (0: none)
   int device = -1;
   std::vector<uint8_t> marks;
-  std::vector<hipEvent_t> pending;     // one per tracked launch of this iteration
-  std::vector<hipEvent_t> pool;        // recycled events
+  // Streams that carried tracked launches of this iteration (nearly always one).  Work enqueued later on the
+  // same stream runs after them by stream order; another stream is made to wait through an event recorded
+  // when the wait is needed, so a tracked launch costs no event of its own.
+  std::vector<hipStream_t> streams;
+  std::vector<hipEvent_t> pool;        // events for cross-stream waits, reused
   std::mutex mu;
 };
 
+// The host waits until every tracked launch of this iteration has finished.
 int tracker_wait(Tracker &t) {
-  for (hipEvent_t e : t.pending) SWIFT_HIP(hipEventSynchronize(e));
+  for (hipStream_t s : t.streams) SWIFT_HIP(hipStreamSynchronize(s));
   return SWIFT_OK;
 }
 
-void tracker_recycle(Tracker &t) {
-  t.pool.insert(t.pool.end(), t.pending.begin(), t.pending.end());
-  t.pending.clear();
+// `stream` waits, on the device, for every tracked launch of this iteration.
+int tracker_order_after(Tracker &t, hipStream_t stream) {
+  size_t used = 0;
+  for (hipStream_t s : t.streams) {
+    if (s == stream) continue;
+    if (used == t.pool.size()) {
+      hipEvent_t e;
+      SWIFT_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      t.pool.push_back(e);
+    }
+    hipEvent_t e = t.pool[used++];
+    SWIFT_HIP(hipEventRecord(e, s));
+    SWIFT_HIP(hipStreamWaitEvent(stream, e, 0));
+  }
+  return SWIFT_OK;
 }
 
 }  // namespace
@@ -1574,16 +1590,14 @@ int swift_tracker_create(int64_t n_tensors, swift_tracker **out) {
 int swift_tracker_destroy(swift_tracker *tr) {
   if (!tr) return SWIFT_OK;
   Tracker &t = tr->t;
-  int rc = SWIFT_OK;
   {
     std::lock_guard<std::mutex> lock(t.mu);
-    rc = tracker_wait(t);              // launched kernels finish before their events go away
-    tracker_recycle(t);
+    // launches in flight own nothing of the tracker's (an event may be destroyed while a stream still waits for it)
     for (hipEvent_t e : t.pool) (void)hipEventDestroy(e);
     t.pool.clear();
   }
   delete tr;
-  return rc;
+  return SWIFT_OK;
 }
 
 int swift_tracker_begin(swift_tracker *tr, int64_t step) {
@@ -1593,7 +1607,7 @@ int swift_tracker_begin(swift_tracker *tr, int64_t step) {
   std::lock_guard<std::mutex> lock(t.mu);
   // the previous iteration's update is complete on every replica once the next one begins (the
   // paper's argument for keeping a single gradient version): its marks are dropped
-  tracker_recycle(t);
+  t.streams.clear();
   std::fill(t.marks.begin(), t.marks.end(), 0);
   t.step = step;
   return SWIFT_OK;
@@ -1645,35 +1659,11 @@ int swift_tracker_step(swift_tracker *tr, const swift_tensor_list *group, const 
     // everything that can be refused is checked before anything is enqueued, the stream wait included
     OptLaunch launch;
     if (int rc = opt_prepare(group, hp, nullptr, nullptr, false, false, stream, &launch)) return rc;
-    hipEvent_t done;
-    if (!t.pool.empty()) {
-      done = t.pool.back();
-      t.pool.pop_back();
-    } else {
-      SWIFT_HIP(hipEventCreateWithFlags(&done, hipEventDisableTiming));
-    }
     // the update waits (on the device) for the gradient to be final, as the paper's loop waits for the
     // all-reduce of that tensor before launching its update kernels
-    if (grad_ready_event) {
-      hipError_t e = hipStreamWaitEvent(stream, static_cast<hipEvent_t>(grad_ready_event), 0);
-      if (e != hipSuccess) {
-        t.pool.push_back(done);
-        return fail(SWIFT_EHIP, "hipStreamWaitEvent failed: %s", hipGetErrorName(e));
-      }
-    }
-    const int rc = opt_launch(launch, stream);
-    if (rc != SWIFT_OK) {
-      t.pool.push_back(done);
-      return rc;                         // the launch itself failed (SWIFT_EHIP): nothing is marked
-    }
-    hipError_t e = hipEventRecord(done, stream);
-    if (e != hipSuccess) {
-      // the kernels are in flight but cannot be tracked by an event: wait for them here, then mark
-      (void)hipStreamSynchronize(stream);
-      t.pool.push_back(done);
-    } else {
-      t.pending.push_back(done);
-    }
+    if (grad_ready_event) SWIFT_HIP(hipStreamWaitEvent(stream, static_cast<hipEvent_t>(grad_ready_event), 0));
+    if (int rc = opt_launch(launch, stream)) return rc;   // the launch itself failed (SWIFT_EHIP): nothing is marked
+    if (std::find(t.streams.begin(), t.streams.end(), stream) == t.streams.end()) t.streams.push_back(stream);
     rollback.armed = false;
     for (int64_t k = 0; k < group->n; ++k) t.marks[(size_t)tensor_ids[k]] = 1;
     return SWIFT_OK;
@@ -1701,11 +1691,14 @@ int swift_tracker_undo(swift_tracker *tr, const swift_tensor_list *list, const s
     if (t.step == 0 || hp->step != t.step)
       return fail(SWIFT_EINVAL, "tracker: hparams.step = %lld but iteration %lld is in progress", (long long)hp->step,
                   (long long)t.step);
-    int rc = tracker_wait(t);
-    if (rc) return rc;
-    rc = swift_opt_undo(list, hp, t.marks.data(), hip_stream);
-    if (rc) return rc;
-    tracker_recycle(t);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // the kernels already launched run to completion first (Implementation, "Update-undo"): by stream order,
+    // or through an event where they went to another stream; the host does not wait
+    OptLaunch launch;
+    if (int rc = opt_prepare(list, hp, t.marks.data(), nullptr, false, true, stream, &launch)) return rc;
+    if (int rc = tracker_order_after(t, stream)) return rc;
+    if (int rc = opt_launch(launch, stream)) return rc;
+    t.streams.clear();
     std::fill(t.marks.begin(), t.marks.end(), 0);   // the state is back at the start of the iteration
     return SWIFT_OK;
   });

@@ -113,3 +113,49 @@ def test_layerwise_update_failure_and_undo(B, synth):
     with pytest.raises(B.SwiftError):                           # the full list must match the tracker
         tr.undo(lists[0], hp)
     tr.close()
+
+
+def test_undo_is_ordered_behind_launches_on_other_streams(B, synth):
+    """Tracked launches go to two side streams that are kept busy; the undo is enqueued on a third stream right
+    away, without a host wait in between.  It must still run after every tracked launch: the state ends with the
+    bits of the same flow run on one stream with a host synchronisation between step and undo (the flow that the
+    test above checks against the oracle)."""
+    w = synth.workloads()["resnet50_adam"]
+    n = len(w.shapes)
+    hp = binding_hparams(B, w.kind, dict(w.hyper, step=4))
+    groups = _groups(n, 9)
+    stepped = groups[:12]
+
+    def flow(concurrent):
+        s = synth.make_state(w, "cuda")
+        full = B.TensorList(s.theta, s.grad, s.m, s.v)
+        lists = [B.TensorList([s.theta[i] for i in g], [s.grad[i] for i in g], [s.m[i] for i in g],
+                              [s.v[i] for i in g]) for g in stepped]
+        tr = B.Tracker(n)
+        tr.begin(4)
+        if concurrent:
+            side = [torch.cuda.Stream(), torch.cuda.Stream()]
+            third = torch.cuda.Stream()
+            a = torch.randn(4096, 4096, device="cuda")
+            torch.cuda.synchronize()
+            for st in side:                                     # a few milliseconds of work ahead of the updates
+                with torch.cuda.stream(st):
+                    for _ in range(6):
+                        a @ a
+            for k, (g, tl) in enumerate(zip(stepped, lists)):
+                tr.step(tl, g, hp, stream=side[k % 2])
+            tr.undo(full, hp, stream=third)
+        else:
+            for g, tl in zip(stepped, lists):
+                tr.step(tl, g, hp)
+            torch.cuda.synchronize()
+            tr.undo(full, hp)
+        torch.cuda.synchronize()
+        assert tr.marks() == [0] * n
+        tr.close()
+        return s
+
+    ref, got = flow(False), flow(True)
+    for name in ("theta", "m", "v"):
+        for i, (a_, b_) in enumerate(zip(getattr(ref, name), getattr(got, name))):
+            assert torch.equal(a_.view(torch.int32), b_.view(torch.int32)), (name, i)
