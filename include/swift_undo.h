@@ -229,7 +229,7 @@ int swift_lamb_undo(const swift_tensor_list *list, const swift_hparams *hp, cons
  * shard_elems = 0: one shard per buffer (numel < 2^32 required); otherwise 0 < shard_elems < 2^32
  * and a buffer is cut into consecutive shards of that many words, the last one short.
  * out_device: DEVICE, swift_digest_count(...) entries, buffer-major; fully overwritten.
- * Shards longer than the kernel's chunk (4 Ki to 256 Ki words, by total size) are summed in two launches
+ * Shards longer than the kernel's chunk (4 Ki to 64 Ki words, by total size) are summed in two launches
  * through per-list scratch (8 bytes per chunk): calls on the same buffer list must not overlap in time. */
 int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *numel,
                        int64_t shard_elems, uint64_t *out_device, void *hip_stream);
