@@ -81,6 +81,38 @@ __device__ __forceinline__ uint64_t wave_sum_u64(uint64_t s) {
   return total;
 }
 
+// The same value summed over the four rows: every lane ends with the sum of lanes l, l^16, l^32 and l^48.
+// v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second, so with both
+// operands equal to r the two results are {row0, row0, row2, row2} and {row1, row1, row3, row3};
+// v_permlane32_swap does the same with the two halves of the wavefront.
+__device__ __forceinline__ uint64_t rows_sum_u64(uint64_t r) {
+  uint32_t lo = (uint32_t)r, hi = (uint32_t)(r >> 32);
+  auto pl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+  auto ph = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+  const uint64_t s = (((uint64_t)ph[0] << 32) | pl[0]) + (((uint64_t)ph[1] << 32) | pl[1]);
+  lo = (uint32_t)s;
+  hi = (uint32_t)(s >> 32);
+  pl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+  ph = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+  return (((uint64_t)ph[0] << 32) | pl[0]) + (((uint64_t)ph[1] << 32) | pl[1]);
+}
+
+// Three sums over the wavefront at once (mod 2^64): afterwards lane l holds the sum of a if l % 4 == 0, of b if
+// l % 4 == 1, of c otherwise.  Summing each value on its own takes 3 x 4 exchanges inside the rows; here the first
+// two exchanges also halve the number of live values (a lane keeps one value and sends the other one to its
+// partner, which keeps that one), so the remaining exchanges move a single register: 7 exchanges instead of 12,
+// and one pass over the rows instead of three.
+__device__ __forceinline__ uint64_t wave_sum3_u64(uint64_t a, uint64_t b, uint64_t c) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const bool odd = (lane & 1u) != 0, upper = (lane & 2u) != 0;
+  const uint64_t ab = (odd ? b : a) + dpp_fetch_u64<0xB1>(odd ? a : b);   // lane ^ 1: even lanes a, odd lanes b
+  const uint64_t cc = c + dpp_fetch_u64<0xB1>(c);
+  uint64_t r = (upper ? cc : ab) + dpp_fetch_u64<0x4E>(upper ? ab : cc);  // lane ^ 2: a, b, c, c within each quad
+  r += dpp_fetch_u64<0x124>(r);                                           // row_ror:4  (keeps lane % 4)
+  r += dpp_fetch_u64<0x128>(r);                                           // row_ror:8  -> sums over the row
+  return rows_sum_u64(r);
+}
+
 __global__ void __launch_bounds__(kThreads) fill_u64_kernel(uint64_t *p, uint64_t n, uint64_t value) {
   for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kThreads)
     p[i] = value;

@@ -4,8 +4,8 @@
 // the state at the last completed iteration.  Computing them in a pass of their own re-reads
 // theta, m and v (12 bytes per parameter, 45 % on top of an Adam step); here the kernel that
 // writes the new state also mixes the words it writes, so the reference digests cost no HBM
-// traffic beyond 24 bytes per tile.  Per tile the three lane sums are combined by DPP and lane reads
-// and stored in the tile's slot; two small kernels then add the tile slots of each chunk and the
+// traffic beyond 24 bytes per tile.  Per tile the three lane sums are combined in one pass of lane
+// exchanges (DPP inside the rows, lane swaps across them) and stored in the tile's slot; two small kernels then add the tile slots of each chunk and the
 // chunk sums of each tensor (order-free: the digest is a sum mod 2^64).  The results equal what
 // swift_state_digest returns for the same buffers with one shard per buffer.
 // The kernel is bound by instruction issue, not by HBM: about 48 vector instructions of update
@@ -58,14 +58,9 @@ opt_digest_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32
     if (ti * TILE >= d.len) continue;
     OptDigestOp<KIND, UNDO, XB> op{c, d.elem0 + (uint32_t)(kK1 >> 32)};
     process_tile<OptDigestOp<KIND, UNDO, XB>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
-    const uint64_t sx = wave_sum_u64(op.dx), sm = wave_sum_u64(op.dm);
-    const uint64_t sv = (KIND != kSGDM) ? wave_sum_u64(op.dv) : 0;
-    if (threadIdx.x == 0) {
-      uint64_t *slot = tile_digest + 3 * w;
-      st<false>(slot, sx);
-      st<false>(slot + 1, sm);
-      if constexpr (KIND != kSGDM) st<false>(slot + 2, sv);
-    }
+    // lanes 0, 1, 2 end with the theta, m and v sums and store them side by side
+    const uint64_t sum = wave_sum3_u64(op.dx, op.dm, op.dv);
+    if (threadIdx.x < (KIND != kSGDM ? 3u : 2u)) st<false>(tile_digest + 3 * w + threadIdx.x, sum);
   } while ((w += gridDim.x) < n_slots);
 }
 
