@@ -794,9 +794,9 @@ int opt_launch(const OptLaunch &L, hipStream_t stream) {
   // The host cannot size the grid to the marked tensors, and a workgroup that finds nothing to do
   // still costs a dispatch (about 0.9 ns) plus the latency of the table fetch it needed to find that
   // out.  So a small kernel first packs the chunk table by the mask, entirely on the device, and
-  // leaves the slot count beside it; the update kernel then runs over the packed table with a
-  // capped grid, strides, and stops at that count: every pass of its loop has a tile to process,
-  // and an almost empty mask costs at most the capped grid's idle dispatches.
+  // leaves the slot count beside it (and clears the tile counters); the update kernel then runs
+  // over the packed table and stops at that count, so every tile it takes is a marked one
+  // (launch_packed: resident wavefronts that draw tiles from the counters, or a capped strided grid).
   char *pm = static_cast<char *>(plan.packed_mem);
   ChunkDesc *packed = reinterpret_cast<ChunkDesc *>(pm + plan.packed_table_off);
   uint64_t *count = reinterpret_cast<uint64_t *>(pm + plan.packed_count_off);
