@@ -28,21 +28,28 @@ struct TensorSpan {        // one per tensor of the caller's list, device reside
   uint32_t pad;
 };
 
-// Sum over the 64 lanes in a fixed order; the result is wave-uniform.
-__device__ __forceinline__ double wave_sum_f64(double s) {
-  s += __longlong_as_double((long long)dpp_fetch_u64<0xB1>((uint64_t)__double_as_longlong(s)));
-  s += __longlong_as_double((long long)dpp_fetch_u64<0x4E>((uint64_t)__double_as_longlong(s)));
-  s += __longlong_as_double((long long)dpp_fetch_u64<0x141>((uint64_t)__double_as_longlong(s)));
-  s += __longlong_as_double((long long)dpp_fetch_u64<0x140>((uint64_t)__double_as_longlong(s)));
-  double row[4];
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const uint64_t bits = (uint64_t)__double_as_longlong(s);
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, k * 16);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(bits >> 32), k * 16);
-    row[k] = __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
-  }
-  return (row[0] + row[1]) + (row[2] + row[3]);
+// Two sums over the 64 lanes at once, in a fixed order: afterwards lane 0 holds the sum of a and lane 1 the sum
+// of b (every even lane holds a sum of a, every odd lane one of b, formed in lane-dependent but fixed order).
+// In the first exchange a lane keeps one of its two values and hands the other to its partner, which keeps that
+// one; from then on a single register moves, and the rows are combined by lane swaps instead of lane reads.
+__device__ __forceinline__ double wave_sum2_f64(double a, double b) {
+  const bool odd = (threadIdx.x & 1u) != 0;
+  auto bits = [](double x) { return (uint64_t)__double_as_longlong(x); };
+  auto dbl = [](uint64_t x) { return __longlong_as_double((long long)x); };
+  double r = (odd ? b : a) + dbl(dpp_fetch_u64<0xB1>(bits(odd ? a : b)));   // lane ^ 1
+  r += dbl(dpp_fetch_u64<0x4E>(bits(r)));                                    // lane ^ 2
+  r += dbl(dpp_fetch_u64<0x124>(bits(r)));                                   // row_ror:4 (keeps the lane's parity)
+  r += dbl(dpp_fetch_u64<0x128>(bits(r)));                                   // row_ror:8 -> sums over the row
+  // rows: v_permlane16_swap gives {row0, row0, row2, row2} and {row1, row1, row3, row3}, v_permlane32_swap the halves
+  uint32_t lo = (uint32_t)bits(r), hi = (uint32_t)(bits(r) >> 32);
+  auto pl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+  auto ph = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+  r = dbl(((uint64_t)ph[0] << 32) | pl[0]) + dbl(((uint64_t)ph[1] << 32) | pl[1]);
+  lo = (uint32_t)bits(r);
+  hi = (uint32_t)(bits(r) >> 32);
+  pl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+  ph = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+  return dbl(((uint64_t)ph[0] << 32) | pl[0]) + dbl(((uint64_t)ph[1] << 32) | pl[1]);
 }
 
 // Pass 1 of the step: the moment recurrences (written back) and the running sums for the norms.
@@ -99,8 +106,8 @@ lamb_moments_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint
     if (ti * TILE >= d.len) continue;          // slot past the end of a short chunk
     LambMomentsOp op{c};
     process_tile<LambMomentsOp, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
-    const double sx = wave_sum_f64(op.sx), su = wave_sum_f64(op.su);
-    if (threadIdx.x == 0) partial[w] = make_double2(sx, su);
+    const double sum = wave_sum2_f64(op.sx, op.su);           // lane 0: sum x^2, lane 1: sum u^2
+    if (threadIdx.x < 2) reinterpret_cast<double *>(partial)[2 * w + threadIdx.x] = sum;
   } while ((w += gridDim.x) < n_slots);
 }
 
