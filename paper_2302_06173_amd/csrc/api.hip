@@ -75,6 +75,7 @@ struct Knobs {
   long tile_u, tile_block, waves_per_cu, chunk_elems, dmask_wgs_per_cu, dmask_queue, dmask_counters, dmask_queue_waves;
   long digest_chunk_elems, digest_waves_per_cu, copy_u, copy_waves_per_cu;
   long lamb_u1, lamb_u3, lamb_waves_p1, lamb_waves_p3, fused_u, fused_waves_per_cu;
+  long max_grid;   // 0: none.  Tests set it to drive the kernels' strided loops, which only lists beyond 2^32 work-items reach
 };
 
 Knobs read_knobs() {
@@ -97,6 +98,7 @@ Knobs read_knobs() {
   k.lamb_waves_p3 = env_long("SWIFT_LAMB_WAVES_P3", SWIFT_LAMB_WAVES_P3);
   k.fused_u = env_long("SWIFT_FUSED_U", SWIFT_FUSED_U);
   k.fused_waves_per_cu = env_long("SWIFT_FUSED_WAVES_PER_CU", SWIFT_FUSED_WAVES_PER_CU);
+  k.max_grid = env_long("SWIFT_MAX_GRID", 0);
   return k;
 }
 
@@ -386,6 +388,16 @@ uint32_t lds_cap_bytes(const DeviceInfo &info, const Tuning &t) {
   const int w = wgs < 3 ? 3 : wgs;                      // stay within the 64 KiB a launch may ask for
   uint32_t bytes = (uint32_t)(info.lds_per_cu / w) & ~511u;
   return bytes > 65536u ? 65536u : bytes;
+}
+
+// Workgroups of a launch over `items` work items, one each -- but a grid holds fewer than 2^32 work-items in
+// all, so beyond that the grid is capped and the kernels, which all stride by the grid size, go round again.
+// (64-lane workgroups: 67 M tiles, i.e. lists above 17 G elements.)
+uint32_t grid_for(uint64_t items, uint32_t block) {
+  uint64_t cap = 0xffffffffull / block;
+  const long forced = knobs().max_grid;
+  if (forced > 0) cap = std::min<uint64_t>(cap, (uint64_t)forced);
+  return (uint32_t)std::min<uint64_t>(items, cap);
 }
 
 // Chunk length: a power of two that is a multiple of every compiled tile (at most 1,024 elements).
@@ -773,7 +785,7 @@ int launch_packed(OptPackedKernel packed_kernel, OptQueueKernel queue_kernel, co
     SWIFT_HIP(hipGetLastError());
     return SWIFT_OK;
   }
-  uint64_t grid_cap = 0x7fffffffull;
+  uint64_t grid_cap = 0xffffffffull / (uint64_t)tune.block;
   if (kn.dmask_wgs_per_cu > 0) grid_cap = (uint64_t)info.cus * (uint64_t)kn.dmask_wgs_per_cu;
   hipLaunchKernelGGL(packed_kernel, dim3((uint32_t)std::min<uint64_t>(n_slots, grid_cap)), dim3((uint32_t)tune.block),
                      lds_cap_bytes(info, tune), stream, packed, count, tpc_shift, c);
@@ -786,7 +798,7 @@ int opt_launch(const OptLaunch &L, hipStream_t stream) {
   const Plan &plan = *L.plan;
   const ChunkDesc *table = static_cast<const ChunkDesc *>(plan.chunks());
   if (!L.packed_kernel) {
-    hipLaunchKernelGGL(L.kernel, dim3((uint32_t)std::min<uint64_t>(L.n_slots, 0x7fffffffull)), dim3((uint32_t)L.tune.block),
+    hipLaunchKernelGGL(L.kernel, dim3(grid_for(L.n_slots, (uint32_t)L.tune.block)), dim3((uint32_t)L.tune.block),
                        lds_cap_bytes(L.info, L.tune), stream, table, L.n_slots, L.tpc_shift, L.c);
     SWIFT_HIP(hipGetLastError());
     return SWIFT_OK;
@@ -1102,14 +1114,14 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
     if (plan->n_chunks == 0) return SWIFT_OK;
     const auto k = bf16 ? (xb ? lamb_undo_kernel<true, true, 1, 64> : lamb_undo_kernel<true, false, 1, 64>)
                         : (xb ? lamb_undo_kernel<false, true, 1, 64> : lamb_undo_kernel<false, false, 1, 64>);
-    hipLaunchKernelGGL(k, dim3((uint32_t)std::min<uint64_t>(slotsu, 0x7fffffffull)), dim3(64), lds_cap_bytes(info, tu),
+    hipLaunchKernelGGL(k, dim3(grid_for(slotsu, 64)), dim3(64), lds_cap_bytes(info, tu),
                        stream, chunks, slotsu, su, c, static_cast<const double *>(norms));
     SWIFT_HIP(hipGetLastError());
     return SWIFT_OK;
   }
   if ((rc = lamb_prepare(*plan, tile1, stream))) return rc;
   if (plan->n_chunks) {
-    hipLaunchKernelGGL(pick_lamb_moments(u1, bf16), dim3((uint32_t)std::min<uint64_t>(slots1, 0x7fffffffull)), dim3(64),
+    hipLaunchKernelGGL(pick_lamb_moments(u1, bf16), dim3(grid_for(slots1, 64)), dim3(64),
                        lds_cap_bytes(info, t1), stream, chunks, slots1, s1, c, static_cast<double2 *>(plan->lamb_partial));
     SWIFT_HIP(hipGetLastError());
   }
@@ -1117,7 +1129,7 @@ int lamb_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t
                      static_cast<const TensorSpan *>(plan->lamb_spans), static_cast<const double2 *>(plan->lamb_partial), norms);
   SWIFT_HIP(hipGetLastError());
   if (plan->n_chunks) {
-    hipLaunchKernelGGL(pick_lamb_apply(u3, xb), dim3((uint32_t)std::min<uint64_t>(slots3, 0x7fffffffull)), dim3(64),
+    hipLaunchKernelGGL(pick_lamb_apply(u3, xb), dim3(grid_for(slots3, 64)), dim3(64),
                        lds_cap_bytes(info, t3), stream, chunks, slots3, s3, c, static_cast<const double *>(norms));
     SWIFT_HIP(hipGetLastError());
   }
@@ -1229,7 +1241,7 @@ int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_
     const uint32_t shift = shift_for(tile_elems, plan->chunk_elems);
     const uint64_t n_slots = (uint64_t)plan->n_chunks << shift;
     const ChunkDesc *table = static_cast<const ChunkDesc *>(plan->chunks());
-    hipLaunchKernelGGL(fused_kernel, dim3((uint32_t)std::min<uint64_t>(n_slots, 0x7fffffffull)),
+    hipLaunchKernelGGL(fused_kernel, dim3(grid_for(n_slots, 64)),
                        dim3(64), lds_cap_bytes(info, tune), stream, table, n_slots, shift, c, tiles);
     SWIFT_HIP(hipGetLastError());
     hipLaunchKernelGGL(chunk_digest_kernel, dim3(plan->n_chunks), dim3(kThreads), 0, stream, table, shift, tile_elems,
@@ -1487,7 +1499,7 @@ int swift_state_digest(int64_t n_buf, const void *const *buf, const int64_t *num
       SWIFT_HIP(hipGetLastError());
     }
     if (plan->n_chunks) {
-      const uint32_t grid = plan->n_chunks;                      // one workgroup per chunk
+      const uint32_t grid = grid_for(plan->n_chunks, kThreads);  // one workgroup per chunk
       const Tuning dtune{1, kThreads, (int)knobs().digest_waves_per_cu};
       hipLaunchKernelGGL(digest_kernel, dim3(grid), dim3(kThreads), lds_cap_bytes(info, dtune), stream,
                          static_cast<const DigestDesc *>(plan->descs()), static_cast<const ChunkRef *>(plan->chunks()),
@@ -1557,7 +1569,7 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
     const uint64_t n16 = (uint64_t)bytes / 16;
     const uint64_t tile = (uint64_t)u * SWIFT_DEFAULT_BLOCK;
     const uint64_t tiles = (n16 + tile - 1) / tile;
-    const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, 0x7fffffffull);
+    const uint32_t grid = grid_for(tiles, SWIFT_DEFAULT_BLOCK);
     const auto launch = [&](auto kernel) {
       hipLaunchKernelGGL(kernel, dim3(grid), dim3(SWIFT_DEFAULT_BLOCK), lds_cap_bytes(info, tune),
                          static_cast<hipStream_t>(hip_stream), static_cast<u32x4 *>(dst_device),
