@@ -101,7 +101,7 @@ typedef struct {
   int32_t reserved;     /* must be 0 */
 } swift_hparams;
 
-/* A list of n tensors.  All arrays are HOST arrays of length n; the pointers they hold are
+/* A list of n tensors (0 <= n < 2^24).  All arrays are HOST arrays of length n; the pointers they hold are
  * DEVICE pointers to contiguous 1-D storage of numel[i] elements.  param, m, v: binary32,
  * 4-byte aligned, updated in place.  grad: binary32 (4-byte aligned) or bfloat16 (2-byte
  * aligned), NEVER written -- the undo needs it intact (paper, "Update-undo": only the latest

@@ -335,6 +335,7 @@ void key_add(std::string &k, const T &v) { k.append(reinterpret_cast<const char 
 // No buffer of this library's callers can be longer (4 TiB of binary32); the bound keeps byte counts
 // and chunk counts derived from a corrupt numel far away from integer overflow.
 constexpr int64_t kMaxNumel = (int64_t)1 << 40;
+constexpr int64_t kMaxTensors = ((int64_t)1 << 24) - 1;
 
 // A device range [p, p + bytes) must lie inside one allocation of the current device.
 int check_device_range(const void *p, size_t bytes, int dev, const char *what, int64_t idx) {
@@ -507,7 +508,8 @@ int validate_hparams(const swift_hparams *hp, bool undo, OptConsts *c) {
 
 int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
   if (!l) return fail(SWIFT_EINVAL, "tensor list is NULL");
-  if (l->n < 0 || l->n > (int64_t)0x7fffffff) return fail(SWIFT_EINVAL, "tensor count %lld out of range", (long long)l->n);
+  // (several launches take one 256-lane workgroup per tensor, and a grid holds fewer than 2^32 work-items)
+  if (l->n < 0 || l->n > kMaxTensors) return fail(SWIFT_EINVAL, "tensor count %lld out of range (at most %lld)", (long long)l->n, (long long)kMaxTensors);
   if (l->n == 0) return SWIFT_OK;
   if (!l->param || !l->grad || !l->m || !l->numel) return fail(SWIFT_EINVAL, "param, grad, m and numel arrays must not be NULL");
   const bool hasv = hp->kind != SWIFT_SGDM;
