@@ -806,7 +806,7 @@ int opt_launch(const OptLaunch &L, hipStream_t stream) {
     return SWIFT_OK;
   }
   // The host cannot size the grid to the marked tensors, and a workgroup that finds nothing to do
-  // still costs a dispatch (about 0.9 ns) plus the latency of the table fetch it needed to find that
+  // still costs a dispatch (0.2-0.3 ns) plus the latency of the table fetch it needed to find that
   // out.  So a small kernel first packs the chunk table by the mask, entirely on the device, and
   // leaves the slot count beside it (and clears the tile counters); the update kernel then runs
   // over the packed table and stops at that count, so every tile it takes is a marked one
