@@ -5,7 +5,7 @@ leg of ``bench.py`` may import this package; the GPU library and its Python bind
 never do, and this package imports nothing from them.
 
 The arithmetic lives in ``swift_oracle.c`` (plain scalar binary64 loops, one function
-per algorithm of the paper: Alg. 1, Alg. 2 and the six algorithms of App. A; plus LAMB
+per algorithm of the paper: Alg. 1, Alg. 2 and the six algorithms of App. A (SGD, Adam, AdamW and their undos); plus LAMB
 with the saved-norm undo that the paper's "Update-undo" section sketches in one sentence).
 This module only compiles that file with gcc, widens inputs to fp64 and walks tensor lists.
 
@@ -34,7 +34,7 @@ _SRC = os.path.join(_HERE, "swift_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
-SGDM, ADAM, ADAMW, LAMB = "sgdm", "adam", "adamw", "lamb"
+SGD, SGDM, ADAM, ADAMW, LAMB = "sgd", "sgdm", "adam", "adamw", "lamb"
 
 
 def build(force: bool = False) -> str:
@@ -56,6 +56,8 @@ def _load():
         d, p, i64 = ctypes.c_double, ctypes.c_void_p, ctypes.c_int64
         lib.oracle_sgdm_step.argtypes = [i64, p, p, p, d, d, d, d, p, p]
         lib.oracle_sgdm_undo.argtypes = [i64, p, p, p, d, d, d, d, p, p]
+        lib.oracle_sgd_step.argtypes = lib.oracle_sgd_undo.argtypes = [i64, p, p, d, d, p]
+        lib.oracle_sgd_step.restype = lib.oracle_sgd_undo.restype = None
         for name in ("adam_step", "adam_undo", "adamw_step", "adamw_undo"):
             getattr(lib, "oracle_" + name).argtypes = [i64, p, p, p, p, d, d, d, d, d, i64, p, p, p]
         for name in ("sgdm_step", "sgdm_undo", "adam_step", "adam_undo", "adamw_step", "adamw_undo"):
@@ -76,7 +78,7 @@ def _load():
 @dataclass
 class Hyper:
     """Hyper-parameters in the paper's notation (the oracle's own type)."""
-    kind: str                 # "sgdm" | "adam" | "adamw"
+    kind: str                 # "sgd" | "sgdm" | "adam" | "adamw"
     eta: float                # learning rate eta_t
     lam: float = 0.0          # weight decay lambda
     mu: float = 0.0           # momentum (SGDM)
@@ -108,6 +110,13 @@ def _ptr(a: np.ndarray):
 
 def _run(which: str, hp: Hyper, x, g, m, v):
     lib = _load()
+    if hp.kind == SGD:                        # App. A "SGD" / "Undo SGD": no optimizer state
+        x, g = widen(x), widen(g)
+        if g.size != x.size:
+            raise ValueError("oracle: x, g differ in size")
+        xo = np.empty(x.size)
+        getattr(lib, f"oracle_sgd_{which}")(x.size, _ptr(x), _ptr(g), hp.eta, hp.lam, _ptr(xo))
+        return xo, None, None
     x, g, m = widen(x), widen(g), widen(m)
     n = x.size
     if g.size != n or m.size != n:
@@ -129,20 +138,20 @@ def _run(which: str, hp: Hyper, x, g, m, v):
     return xo, mo, vo
 
 
-def opt_step(hp: Hyper, x, g, m, v=None):
-    """(x_t, g_t, m_{t-1}, v_{t-1}) -> (x_{t+1}, m_t, v_t), all fp64 (v is None for SGDM)."""
+def opt_step(hp: Hyper, x, g, m=None, v=None):
+    """(x_t, g_t, m_{t-1}, v_{t-1}) -> (x_{t+1}, m_t, v_t), all fp64 (v is None for SGDM, m and v for SGD)."""
     return _run("step", hp, x, g, m, v)
 
 
-def opt_undo(hp: Hyper, x_new, g, m_new, v_new=None):
+def opt_undo(hp: Hyper, x_new, g, m_new=None, v_new=None):
     """(x_{t+1}, g_t, m_t, v_t) -> (x_t, m_{t-1}, v_{t-1}), all fp64.
 
     Raises ZeroDivisionError where the printed inverse divides by zero and no reading
-    rescues it (beta1 = 0, beta2 = 0, eta*lambda = 1 for AdamW); mu = 0 is allowed.
+    rescues it (beta1 = 0, beta2 = 0, eta*lambda = 1 for AdamW and plain SGD); mu = 0 is allowed.
     """
     if hp.kind in (ADAM, ADAMW) and (hp.beta1 == 0.0 or hp.beta2 == 0.0):
         raise ZeroDivisionError("undo: beta = 0 is not invertible")
-    if hp.kind == ADAMW and 1.0 - hp.eta * hp.lam == 0.0:
+    if hp.kind in (ADAMW, SGD) and 1.0 - hp.eta * hp.lam == 0.0:
         raise ZeroDivisionError("undo: eta*lambda = 1 is not invertible")
     x_old, m_old, v_old = _run("undo", hp, x_new, g, m_new, v_new)
     if hp.clamp_v and v_old is not None:
@@ -185,21 +194,22 @@ def lamb_undo(hp: Hyper, x_new, g, m_new, v_new, norms):
 def _walk(fn, hp, xs, gs, ms, vs, mask):
     out = []
     for i in range(len(xs)):
+        m = None if ms is None else ms[i]
         v = None if vs is None else vs[i]
         if mask is not None and not mask[i]:
-            out.append((widen(xs[i]), widen(ms[i]), None if v is None else widen(v)))
+            out.append((widen(xs[i]), None if m is None else widen(m), None if v is None else widen(v)))
         else:
-            out.append(fn(hp, xs[i], gs[i], ms[i], v))
+            out.append(fn(hp, xs[i], gs[i], m, v))
     return out
 
 
-def step_list(hp: Hyper, xs: Sequence, gs: Sequence, ms: Sequence, vs: Optional[Sequence] = None,
+def step_list(hp: Hyper, xs: Sequence, gs: Sequence, ms: Optional[Sequence] = None, vs: Optional[Sequence] = None,
               mask: Optional[Sequence] = None):
     """Step every tensor whose mask entry is non-zero (all if mask is None); the rest pass through."""
     return _walk(opt_step, hp, xs, gs, ms, vs, mask)
 
 
-def undo_list(hp: Hyper, xs: Sequence, gs: Sequence, ms: Sequence, vs: Optional[Sequence] = None,
+def undo_list(hp: Hyper, xs: Sequence, gs: Sequence, ms: Optional[Sequence] = None, vs: Optional[Sequence] = None,
               mask: Optional[Sequence] = None):
     """Undo every tensor marked as updated (the paper's per-parameter flag); the rest pass through."""
     return _walk(opt_undo, hp, xs, gs, ms, vs, mask)

@@ -67,6 +67,25 @@ void oracle_sgdm_undo(int64_t n, const double *x_new, const double *g, const dou
 }
 
 /* ------------------------------------------------------------------------- */
+/* App. A, Alg. "SGD": x_{t+1} = x_t - eta_t (g_t + lambda x_t).  No optimizer state. */
+void oracle_sgd_step(int64_t n, const double *x, const double *g, double eta, double lambda, double *x_new)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        x_new[i] = x[i] - eta * (g[i] + lambda * x[i]);
+    }
+}
+
+/* App. A, Alg. "Undo SGD": x_t = (x_{t+1} + eta_t g_t) / (1 - eta_t lambda).       */
+/* (The printed line drops the subscript of eta in the denominator; it is the same  */
+/* eta_t.)  eta_t lambda = 1 divides by zero: the caller refuses that case.         */
+void oracle_sgd_undo(int64_t n, const double *x_new, const double *g, double eta, double lambda, double *x_old)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        x_old[i] = (x_new[i] + eta * g[i]) / (1.0 - eta * lambda);
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* App. A, Alg. "Adam" (weight decay coupled into the gradient).                */
 void oracle_adam_step(int64_t n, const double *x, const double *g, const double *m, const double *v,
                       double eta, double lambda, double beta1, double beta2, double eps, int64_t t,

@@ -2,7 +2,7 @@
 
   - hand-worked exact-rational examples (tests/golden/worked_examples.txt);
   - torch.optim's SGD / Adam / AdamW run in fp64 on the CPU: an independent library routine that
-    Alg. 1 (tau-damped momentum with a pre-existing buffer) and App. A's Adam / AdamW (alpha = 1)
+    Alg. 1 (tau-damped momentum with a pre-existing buffer) and App. A's SGD / Adam / AdamW (alpha = 1)
     reduce to;
   - closed forms and symmetries of the update lines;
   - round trips undo(step(s)) = s: bit-exact where every operation is exact in binary64
@@ -51,13 +51,17 @@ def test_worked_example_step_and_undo(case):
         return
     xn, mn, vn = oracle.opt_step(hp, x, g, m, v)
     _close(xn, f("x_new"), rtol=4e-16, atol=1e-16)
-    _close(mn, f("m_new"), rtol=4e-16, atol=1e-16)
+    if m is not None:
+        _close(mn, f("m_new"), rtol=4e-16, atol=1e-16)
+    else:
+        assert mn is None and vn is None          # App. A's plain SGD keeps no state
     if v is not None:
         _close(vn, f("v_new"), rtol=4e-16, atol=1e-16)
     # undo from the stored (not the computed) new state
     xo, mo, vo = oracle.opt_undo(hp, f("x_new"), g, f("m_new"), f("v_new"))
     _close(xo, x, rtol=1e-15, atol=1e-15)
-    _close(mo, m, rtol=1e-15, atol=1e-15)
+    if m is not None:
+        _close(mo, m, rtol=1e-15, atol=1e-15)
     if v is not None:
         _close(vo, v, rtol=1e-15, atol=1e-15)
 
@@ -311,6 +315,59 @@ def test_momentum_zero_is_plain_sgd_and_its_undo():
     assert np.array_equal(mo, mn)
 
 
+# --------------------------------------------------------------------------- App. A "SGD" / "Undo SGD"
+@pytest.mark.parametrize("lam", [0.0, 0.01, 0.5])
+def test_plain_sgd_step_matches_torch_sgd_without_momentum(lam):
+    x, g, _, _ = _rand_state(21)
+    p = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    p.grad = torch.tensor(g, dtype=torch.float64)
+    torch.optim.SGD([p], lr=0.1, momentum=0.0, weight_decay=lam, foreach=False).step()
+    xn, mn, vn = oracle.opt_step(Hyper("sgd", eta=0.1, lam=lam), x, g)
+    assert mn is None and vn is None
+    _close(xn, p.detach().numpy(), rtol=1e-14, atol=1e-18)
+
+
+def test_plain_sgd_equals_momentum_sgd_with_mu_zero_bit_for_bit():
+    # Alg. 1 with mu = 0, tau = 0 performs the same operations on x as App. A's "SGD" (0 * m + g' = g' exactly)
+    x, g, m, _ = _rand_state(22)
+    a, _, _ = oracle.opt_step(Hyper("sgd", eta=0.1, lam=0.01), x, g)
+    b, _, _ = oracle.opt_step(Hyper("sgdm", eta=0.1, lam=0.01, mu=0.0, tau=0.0), x, g, m)
+    assert np.array_equal(a, b)
+
+
+def test_plain_sgd_undo_is_the_printed_closed_form_and_round_trips():
+    x, g, _, _ = _rand_state(23)
+    hp = Hyper("sgd", eta=0.1, lam=0.01)
+    xn, _, _ = oracle.opt_step(hp, x, g)
+    xo, mo, vo = oracle.opt_undo(hp, xn, g)
+    assert mo is None and vo is None
+    # solving x_new = x - eta (g + lam x) for x, digit by digit in exact rational arithmetic
+    from fractions import Fraction as Fr
+    eta, lam = Fr(0.1), Fr(0.01)                 # the binary64 values the oracle received
+    for i in (0, 3, 7, 100, 256):
+        exact = (Fr(float(xn[i])) + eta * Fr(float(g[i]))) / (1 - eta * lam)
+        assert abs(Fr(float(xo[i])) - exact) <= abs(exact) * Fr(1, 2 ** 50) + Fr(1, 10 ** 30)
+    # (outlier gradients move x by ~0.1, so agreement with the originals is to ulps of that)
+    _close(xo, x, rtol=1e-14, atol=1e-16)
+    # dyadic values: every operation is exact, the round trip returns the original bits
+    r = np.random.default_rng(24)
+    xd = r.integers(-2 ** 20, 2 ** 20, 64).astype(F64) / 2 ** 10
+    gd = r.integers(-2 ** 20, 2 ** 20, 64).astype(F64) / 2 ** 12
+    hd = Hyper("sgd", eta=0.5, lam=0.0)
+    back, _, _ = oracle.opt_undo(hd, oracle.opt_step(hd, xd, gd)[0], gd)
+    assert np.array_equal(back, xd)
+    # the sign of the gradient term and the side the divisor is on: a step with g = 0 scales by (1 - eta lam),
+    # the undo by its reciprocal
+    z = np.zeros_like(x)
+    _close(oracle.opt_step(hp, x, z)[0], x * (1 - 0.1 * 0.01), rtol=1e-15, atol=1e-300)
+    _close(oracle.opt_undo(hp, x, z)[0], x / (1 - 0.1 * 0.01), rtol=1e-15, atol=1e-300)
+    # and with lam = 0 the undo adds back exactly what the step took away
+    h0 = Hyper("sgd", eta=0.25, lam=0.0)
+    # (the difference is taken off values of size 0.02-0.1: good to their ulp, 1e-17)
+    _close(oracle.opt_undo(h0, x, g)[0] - x, 0.25 * g, rtol=1e-12, atol=3e-17)
+    _close(oracle.opt_step(h0, x, g)[0] - x, -0.25 * g, rtol=1e-12, atol=3e-17)
+
+
 def test_not_invertible_settings_raise():
     x, g, m, v = _rand_state(14, n=8)
     with pytest.raises(ZeroDivisionError):
@@ -319,6 +376,8 @@ def test_not_invertible_settings_raise():
         oracle.opt_undo(Hyper("adamw", eta=1e-3, beta2=0.0), x, g, m, v)
     with pytest.raises(ZeroDivisionError):
         oracle.opt_undo(Hyper("adamw", eta=0.5, lam=2.0), x, g, m, v)
+    with pytest.raises(ZeroDivisionError):
+        oracle.opt_undo(Hyper("sgd", eta=0.5, lam=2.0), x, g)
 
 
 def test_list_walk_respects_mask_and_leaves_inputs_alone():

@@ -27,6 +27,24 @@ def _close(a, b, rtol, atol):
 
 
 @settings(max_examples=60, deadline=None)
+@given(seed=seeds, eta=lr, lam=decay)
+def test_plain_sgd_undo_inverts_step(seed, eta, lam):
+    x, g, _, _ = _state(seed)
+    hp = Hyper("sgd", eta=eta, lam=lam)            # eta * lam <= 0.25: the divisor stays away from zero
+    xn, mn, vn = oracle.opt_step(hp, x, g)
+    assert mn is None and vn is None
+    xo, _, _ = oracle.opt_undo(hp, xn, g)
+    scale = max(np.abs(xn).max(), eta * np.abs(g).max())
+    _close(xo, x, 1e-12, 1e-14 * scale)
+    # App. A's update line by hand, vectorised in numpy
+    _close(xn, x - eta * (g + lam * x), 1e-13, 1e-18)
+    # the step is affine in (x, g): stepping a sum is the sum of steps minus nothing else
+    x2, g2, _, _ = _state(seed + 1)
+    both, _, _ = oracle.opt_step(hp, x + x2, g + g2)
+    _close(both, xn + oracle.opt_step(hp, x2, g2)[0], 1e-12, 1e-15 * max(scale, 1.0))
+
+
+@settings(max_examples=60, deadline=None)
 @given(seed=seeds, eta=lr, lam=decay, mu=unit, tau=st.floats(min_value=0.0, max_value=0.9))
 def test_sgdm_undo_inverts_step(seed, eta, lam, mu, tau):
     x, g, m, _ = _state(seed)
