@@ -286,6 +286,11 @@ def main() -> int:
         norms = torch.zeros(2 * n_t, dtype=torch.float64, device="cuda")
         extra("lamb_step", lambda: B.swift_lamb_step(tl_adam, hp_lamb, norms), 40)
         extra("lamb_undo", lambda: B.swift_lamb_undo(tl_adam, hp_lamb, norms), 28)
+    # App. A's plain SGD: no optimizer state, theta and the gradient only
+    hp_sgd = B.hparams("sgd", step=t_step, lr=0.1, weight_decay=1e-4, grad_bf16=bf16)
+    tl_sgd = None if args.no_extras else B.TensorList(state.theta, state.grad)
+    extra("sgd_step", lambda: B.swift_opt_step(tl_sgd, hp_sgd), 8 + g_bytes)
+    extra("sgd_undo", lambda: B.swift_opt_undo(tl_sgd, hp_sgd), 8 + g_bytes)
     dig = torch.zeros(3 * n_t, dtype=torch.int64, device="cuda")
     extra("adamw_step_with_digest", lambda: B.swift_opt_step_digest(tl_adam, hp_w, dig), 24 + g_bytes)
     extra("adamw_undo_with_digest", lambda: B.swift_opt_undo_digest(tl_adam, hp_w, dig), 24 + g_bytes)

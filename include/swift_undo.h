@@ -59,7 +59,7 @@ typedef enum {
                                 pointer that is not device memory of the current GPU or whose
                                 allocation is shorter than numel elements, misaligned pointer */
   SWIFT_ENOTINVERTIBLE = -2, /* undo only: the inverse divides by zero (beta1 = 0, beta2 = 0, or
-                                eta*lambda = 1 for AdamW) */
+                                eta*lambda = 1 for AdamW and plain SGD) */
   SWIFT_EHIP = -3            /* a HIP runtime call failed (the message carries its error name), or the
                                 library could not get host memory; no C++ exception leaves the library */
 } swift_status;
@@ -69,7 +69,9 @@ typedef enum {
                       mu = 0 is App. A's plain SGD with the damped gradient left in the m buffer. */
   SWIFT_ADAM = 1,  /* App. A "Adam" / "Undo Adam": decay coupled into the gradient, g' = g + lambda x */
   SWIFT_ADAMW = 2, /* App. A "AdamW" / "Undo AdamW": decoupled decay, alpha = 1 */
-  SWIFT_LAMB = 3   /* LAMB with saved norms ("Update-undo" section, Table 1); swift_lamb_* entry points only */
+  SWIFT_LAMB = 3,  /* LAMB with saved norms ("Update-undo" section, Table 1); swift_lamb_* entry points only */
+  SWIFT_SGD = 4    /* App. A "SGD" / "Undo SGD": no optimizer state, theta and the gradient only (12 bytes per
+                      parameter); the undo solves the update line for x_t instead of reading a buffer */
 } swift_opt_kind;
 
 typedef enum { SWIFT_F32 = 0, SWIFT_BF16 = 1 } swift_dtype; /* gradients only */
@@ -107,7 +109,8 @@ typedef struct {
  * aligned), NEVER written -- the undo needs it intact (paper, "Update-undo": only the latest
  * gradient is cached, no extra memory).  16-byte alignment of all of a tensor's pointers
  * (8-byte for bfloat16 buffers) selects the 128-bit access path; results are bit-identical either way.
- * v may be NULL for SWIFT_SGDM.  Tensors with numel 0 are allowed and skipped.
+ * v may be NULL for SWIFT_SGDM and SWIFT_SGD, m for SWIFT_SGD (neither is looked at then).  Tensors with
+ * numel 0 are allowed and skipped.
  * Placement advice (throughput only, never correctness): on MI355X the kernels run 2-10 % faster when
  * param[i], grad[i], m[i], v[i] of a tensor do NOT all start at the same address modulo 8 KiB, e.g. when
  * consecutive buffers of an arena are an odd multiple of 2 KiB apart; allocators that hand out buffers at
@@ -130,6 +133,7 @@ typedef struct {
 
 /* Optimizer step t: (x_t, g_t, m_{t-1}, v_{t-1}) -> (x_{t+1}, m_t, v_t) in place, for every
  * tensor whose mask entry is non-zero (all tensors if the mask is NULL).
+ *   SGD   (App. A "SGD"):    x <- x - eta (g + lambda x)
  *   SGDM  (Alg. 1):          g' = g + lambda x;  m <- mu m + (1-tau) g';  x <- x - eta m
  *   Adam  (App. A "Adam"):   g' = g + lambda x;  m <- beta1 m + (1-beta1) g';
  *                            v <- beta2 v + (1-beta2) g'^2;
@@ -142,6 +146,7 @@ int swift_opt_step(const swift_tensor_list *list, const swift_hparams *hp,
 /* Undo of step t: (x_{t+1}, g_t, m_t, v_t) -> (x_t, m_{t-1}, v_{t-1}) in place, for every tensor
  * marked as updated (mask entry non-zero; all if NULL).  The parameter is recovered first, from
  * the new moments; coupled decay is rebuilt from the recovered parameter.
+ *   SGD   (App. A "Undo SGD"):   x <- (x + eta g) / (1 - eta lambda)
  *   SGDM  (Alg. 2):              x <- x + eta m;  m <- (m - (1-tau)(g + lambda x)) / mu
  *                                (mu = 0: the m buffer is left as it is)
  *   Adam  (App. A "Undo Adam"):  x <- x + eta u;  g' = g + lambda x;
@@ -187,12 +192,12 @@ int swift_opt_undo_dmask_noalloc(const swift_tensor_list *list, const swift_hpar
 
 /* swift_opt_step / swift_opt_undo that also return the digests of the state they leave behind, at no
  * extra HBM traffic: digests_device[g * n + i] is the digest of tensor i's theta (g = 0), m (g = 1) and
- * v (g = 2; SGDM has g = 0, 1 only), one shard per tensor, identical to what swift_state_digest writes
+ * v (g = 2; SGDM has g = 0, 1 only, plain SGD g = 0 only), one shard per tensor, identical to what swift_state_digest writes
  * for the buffer order theta_0..theta_{n-1}, m_0.., v_0.. with shard_elems = 0.  A training loop keeps
  * the digests of the last completed iteration this way; after a failure one swift_state_digest pass and
  * swift_mask_from_digests tell which tensors hold stepped bits (the role of the paper's per-parameter
  * "updated" flag, Implementation, "Update-undo").  Entries of unmarked tensors are left alone.  Every
- * tensor must have fewer than 2^32 elements.  digests_device: DEVICE, 3n (2n for SGDM) entries, 8-byte
+ * tensor must have fewer than 2^32 elements.  digests_device: DEVICE, 3n (2n for SGDM, n for SGD) entries, 8-byte
  * aligned.  The call keeps per-list scratch (24 bytes per 256 elements): calls on one list must not overlap. */
 int swift_opt_step_digest(const swift_tensor_list *list, const swift_hparams *hp, const uint8_t *host_mask,
                           uint64_t *digests_device, void *hip_stream);
@@ -307,7 +312,8 @@ int swift_logging_groups(int64_t n_machines, const double *compute_time, const d
 /* Placement helper, host arithmetic only: byte offsets for the state of n tensors inside ONE device allocation
  * (the caller allocates total_bytes, 256-byte aligned, and carves the buffers out of it), laid out so that the
  * kernels reach their best bandwidth.  offsets[i * S + k] is the offset of stream k of tensor i, with S = 4
- * streams (theta, gradient, m, v) if with_v is non-zero, else 3 (theta, gradient, m); the four buffers of a
+ * streams (theta, gradient, m, v) if with_v is positive, 3 (theta, gradient, m) if it is 0, 2 (theta, gradient:
+ * plain SGD) if it is negative; the buffers of a
  * tensor are adjacent, tensor after tensor.  A buffer of 1 MiB or more occupies its size rounded up to 8 KiB plus
  * 2 KiB, so that consecutive buffers start an odd multiple of 2 KiB apart and theta, g, m, v of a tensor begin in
  * four different quarters of an 8 KiB window; smaller buffers are rounded up to 256 bytes.  Why: a tile of the

@@ -16,10 +16,10 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libswift_undo.so")
 
 SWIFT_OK, SWIFT_EINVAL, SWIFT_ENOTINVERTIBLE, SWIFT_EHIP = 0, -1, -2, -3
-SWIFT_SGDM, SWIFT_ADAM, SWIFT_ADAMW, SWIFT_LAMB = 0, 1, 2, 3
+SWIFT_SGDM, SWIFT_ADAM, SWIFT_ADAMW, SWIFT_LAMB, SWIFT_SGD = 0, 1, 2, 3, 4
 SWIFT_F32, SWIFT_BF16 = 0, 1
 SWIFT_CLAMP_V = 1
-KINDS = {"sgdm": SWIFT_SGDM, "adam": SWIFT_ADAM, "adamw": SWIFT_ADAMW, "lamb": SWIFT_LAMB}
+KINDS = {"sgdm": SWIFT_SGDM, "adam": SWIFT_ADAM, "adamw": SWIFT_ADAMW, "lamb": SWIFT_LAMB, "sgd": SWIFT_SGD}
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -141,10 +141,12 @@ def _ptr_array(tensors: Sequence[torch.Tensor]):
 class TensorList:
     """Marshalled swift_tensor_list; keeps the tensors and the host arrays alive."""
 
-    def __init__(self, param: Sequence[torch.Tensor], grad: Sequence[torch.Tensor], m: Sequence[torch.Tensor],
-                 v: Optional[Sequence[torch.Tensor]] = None, param_bf16: Optional[Sequence[torch.Tensor]] = None):
+    def __init__(self, param: Sequence[torch.Tensor], grad: Sequence[torch.Tensor],
+                 m: Optional[Sequence[torch.Tensor]] = None, v: Optional[Sequence[torch.Tensor]] = None,
+                 param_bf16: Optional[Sequence[torch.Tensor]] = None):
+        """m is None for plain SGD (no optimizer state), v for plain SGD and SGD with momentum."""
         n = len(param)
-        if len(grad) != n or len(m) != n or (v is not None and len(v) != n) or \
+        if len(grad) != n or (m is not None and len(m) != n) or (v is not None and len(v) != n) or \
                 (param_bf16 is not None and len(param_bf16) != n):
             raise ValueError("tensor lists differ in length")
         if param_bf16 is not None:
@@ -153,27 +155,28 @@ class TensorList:
                     raise ValueError(f"tensor {i}: param_bf16 must be a contiguous CUDA bfloat16 tensor of the same size")
         self.grad_bf16 = n > 0 and grad[0].dtype == torch.bfloat16
         for i in range(n):
-            group = [param[i], grad[i], m[i]] + ([v[i]] if v is not None else [])
+            group = [param[i], grad[i]] + ([m[i]] if m is not None else []) + ([v[i]] if v is not None else [])
             for t in group:
                 if not t.is_cuda or not t.is_contiguous():
                     raise ValueError(f"tensor {i}: need contiguous CUDA tensors")
                 if t.numel() != param[i].numel():
                     raise ValueError(f"tensor {i}: numel differs between param, grad and moments")
-            if param[i].dtype != torch.float32 or m[i].dtype != torch.float32 or \
+            if param[i].dtype != torch.float32 or (m is not None and m[i].dtype != torch.float32) or \
                     (v is not None and v[i].dtype != torch.float32):
                 raise ValueError(f"tensor {i}: param, m and v must be float32")
             if grad[i].dtype != (torch.bfloat16 if self.grad_bf16 else torch.float32):
                 raise ValueError(f"tensor {i}: gradients must all be float32 or all bfloat16")
-        self._keep = (list(param), list(grad), list(m), None if v is None else list(v),
+        self._keep = (list(param), list(grad), None if m is None else list(m), None if v is None else list(v),
                       None if param_bf16 is None else list(param_bf16))
         self._xb = None if param_bf16 is None else _ptr_array(param_bf16)
-        self._param, self._grad, self._m = _ptr_array(param), _ptr_array(grad), _ptr_array(m)
+        self._param, self._grad = _ptr_array(param), _ptr_array(grad)
+        self._m = None if m is None else _ptr_array(m)
         self._v = None if v is None else _ptr_array(v)
         self._numel = (ctypes.c_int64 * n)(*[t.numel() for t in param])
         self.n = n
         self.c = SwiftTensorList(
             n, ctypes.cast(self._param, ctypes.POINTER(_P)), ctypes.cast(self._grad, ctypes.POINTER(_P)),
-            ctypes.cast(self._m, ctypes.POINTER(_P)),
+            ctypes.cast(self._m, ctypes.POINTER(_P)) if self._m is not None else None,
             ctypes.cast(self._v, ctypes.POINTER(_P)) if self._v is not None else None,
             ctypes.cast(self._numel, ctypes.POINTER(ctypes.c_int64)),
             ctypes.cast(self._xb, ctypes.POINTER(_P)) if self._xb is not None else None)
@@ -244,7 +247,7 @@ def swift_lamb_undo(tl: TensorList, hp: SwiftHparams, norms: torch.Tensor, host_
 
 
 def _fused(fn, tl: TensorList, hp: SwiftHparams, digests, host_mask, stream) -> torch.Tensor:
-    n_groups = 2 if hp.kind == SWIFT_SGDM else 3
+    n_groups = {SWIFT_SGD: 1, SWIFT_SGDM: 2}.get(hp.kind, 3)
     if digests is None:
         digests = torch.zeros(n_groups * tl.n, dtype=torch.int64, device="cuda")
     elif digests.dtype != torch.int64 or not digests.is_cuda or not digests.is_contiguous() \
@@ -404,13 +407,15 @@ _lib.swift_arena_layout.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_int6
 _lib.swift_arena_layout.restype = ctypes.c_int
 
 
-def swift_arena_layout(numel: Sequence[int], grad_bf16: bool = False, with_v: bool = True):
-    """Byte offsets (one row [theta, g, m(, v)] per tensor) and the total size of an arena that holds the state."""
-    n, s = len(numel), 4 if with_v else 3
+def swift_arena_layout(numel: Sequence[int], grad_bf16: bool = False, with_v: bool = True, with_m: bool = True):
+    """Byte offsets (one row [theta, g(, m(, v))] per tensor) and the total size of an arena that holds the state."""
+    if with_v and not with_m:
+        raise ValueError("a second moment without a first moment is no optimizer of this library")
+    n, s = len(numel), 4 if with_v else (3 if with_m else 2)
     sizes = (ctypes.c_int64 * max(n, 1))(*numel)
     offs = (ctypes.c_int64 * max(n * s, 1))()
     total = ctypes.c_int64()
-    _check(_lib.swift_arena_layout(n, sizes, SWIFT_BF16 if grad_bf16 else SWIFT_F32, 1 if with_v else 0, offs,
+    _check(_lib.swift_arena_layout(n, sizes, SWIFT_BF16 if grad_bf16 else SWIFT_F32, 1 if with_v else (0 if with_m else -1), offs,
                                    ctypes.byref(total)))
     return [list(offs[i * s:(i + 1) * s]) for i in range(n)], total.value
 

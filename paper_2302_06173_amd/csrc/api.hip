@@ -373,11 +373,18 @@ struct Tuning {
   int u, block, waves_per_cu;
 };
 
+// Which state streams an optimizer kind has: plain SGD (App. A) none, SGD with momentum m, the Adam family m and v.
+bool kind_has_m(int kind) { return kind != SWIFT_SGD; }
+bool kind_has_v(int kind) { return kind == SWIFT_ADAM || kind == SWIFT_ADAMW || kind == SWIFT_LAMB; }
+
 Tuning opt_tuning(int kind, bool bf16, bool undo) {
   // Measured optima: the fewer bytes a wavefront moves (SGDM has 3 streams in and 2 out instead of
   // 4 and 3; bf16 gradients halve one stream), the more wavefronts a compute unit wants.
   (void)undo;      // step and undo want the same residency once every load of a tile is issued up front
-  const int waves = (kind == SWIFT_SGDM ? SWIFT_DEFAULT_WAVES_PER_CU_SGDM : SWIFT_DEFAULT_WAVES_PER_CU) + (bf16 ? 1 : 0);
+  const int base = kind == SWIFT_SGD ? SWIFT_DEFAULT_WAVES_PER_CU_SGD
+                 : kind == SWIFT_SGDM ? SWIFT_DEFAULT_WAVES_PER_CU_SGDM : SWIFT_DEFAULT_WAVES_PER_CU;
+  // bf16 gradients: one more (plain SGD, where the gradient is half of what is read: four more, 6.72 TB/s at 28 against 6.60 at 24)
+  const int waves = base + (bf16 ? (kind == SWIFT_SGD ? 4 : 1) : 0);
   const Knobs k = knobs();
   return Tuning{(int)k.tile_u, (int)k.tile_block, k.waves_per_cu == kUnset ? waves : (int)k.waves_per_cu};
 }
@@ -462,7 +469,7 @@ int check_no_overlap(Interval *iv, size_t n) {
 
 int validate_hparams(const swift_hparams *hp, bool undo, OptConsts *c) {
   if (!hp) return fail(SWIFT_EINVAL, "hparams is NULL");
-  if (hp->kind < SWIFT_SGDM || hp->kind > SWIFT_LAMB) return fail(SWIFT_EINVAL, "unknown optimizer kind %d", hp->kind);
+  if (hp->kind < SWIFT_SGDM || hp->kind > SWIFT_SGD) return fail(SWIFT_EINVAL, "unknown optimizer kind %d", hp->kind);
   if (hp->grad_dtype != SWIFT_F32 && hp->grad_dtype != SWIFT_BF16)
     return fail(SWIFT_EINVAL, "unknown gradient dtype %d", hp->grad_dtype);
   if (hp->step < 1) return fail(SWIFT_EINVAL, "step must be >= 1 (got %lld)", (long long)hp->step);
@@ -474,6 +481,12 @@ int validate_hparams(const swift_hparams *hp, bool undo, OptConsts *c) {
   c->clamp_v = (hp->flags & SWIFT_CLAMP_V) ? 1 : 0;
   c->eta = hp->lr;
   c->lam = hp->weight_decay;
+  if (hp->kind == SWIFT_SGD) {                    // App. A "SGD" / "Undo SGD"
+    const double oml = 1.0 - hp->lr * hp->weight_decay;
+    if (undo && oml == 0) return fail(SWIFT_ENOTINVERTIBLE, "undo divides by 1 - lr*weight_decay = 0");
+    c->inv_oml = oml != 0 ? 1.0 / oml : 0.0;
+    return SWIFT_OK;
+  }
   if (hp->kind == SWIFT_SGDM) {
     if (!(hp->momentum >= 0 && hp->momentum <= 1)) return fail(SWIFT_EINVAL, "momentum must be in [0, 1]");
     if (!(hp->dampening >= 0 && hp->dampening <= 1)) return fail(SWIFT_EINVAL, "dampening must be in [0, 1]");
@@ -511,19 +524,20 @@ int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
   // (several launches take one 256-lane workgroup per tensor, and a grid holds fewer than 2^32 work-items)
   if (l->n < 0 || l->n > kMaxTensors) return fail(SWIFT_EINVAL, "tensor count %lld out of range (at most %lld)", (long long)l->n, (long long)kMaxTensors);
   if (l->n == 0) return SWIFT_OK;
-  if (!l->param || !l->grad || !l->m || !l->numel) return fail(SWIFT_EINVAL, "param, grad, m and numel arrays must not be NULL");
-  const bool hasv = hp->kind != SWIFT_SGDM;
+  const bool hasm = kind_has_m(hp->kind), hasv = kind_has_v(hp->kind);
+  if (!l->param || !l->grad || (hasm && !l->m) || !l->numel)
+    return fail(SWIFT_EINVAL, "param, grad, m and numel arrays must not be NULL (m may be NULL for plain SGD only)");
   if (hasv && !l->v) return fail(SWIFT_EINVAL, "Adam/AdamW need the v array");
   const uintptr_t galign = hp->grad_dtype == SWIFT_BF16 ? 1 : 3;
   for (int64_t i = 0; i < l->n; ++i) {
     if (l->numel[i] < 0 || l->numel[i] > kMaxNumel)
       return fail(SWIFT_EINVAL, "numel[%lld] = %lld is negative or beyond 2^40", (long long)i, (long long)l->numel[i]);
     if (l->numel[i] == 0) continue;
-    if (!l->param[i] || !l->grad[i] || !l->m[i] || (hasv && !l->v[i]))
+    if (!l->param[i] || !l->grad[i] || (hasm && !l->m[i]) || (hasv && !l->v[i]))
       return fail(SWIFT_EINVAL, "tensor %lld has a NULL pointer", (long long)i);
     if (l->param_bf16 && (!l->param_bf16[i] || ((uintptr_t)l->param_bf16[i] & 1)))
       return fail(SWIFT_EINVAL, "tensor %lld: param_bf16 is NULL or not 2-byte aligned", (long long)i);
-    if (((uintptr_t)l->param[i] & 3) || ((uintptr_t)l->m[i] & 3) || (hasv && ((uintptr_t)l->v[i] & 3)) ||
+    if (((uintptr_t)l->param[i] & 3) || (hasm && ((uintptr_t)l->m[i] & 3)) || (hasv && ((uintptr_t)l->v[i] & 3)) ||
         ((uintptr_t)l->grad[i] & galign))
       return fail(SWIFT_EINVAL, "tensor %lld has a pointer that is not aligned to its element size", (long long)i);
   }
@@ -532,11 +546,11 @@ int validate_list(const swift_tensor_list *l, const swift_hparams *hp) {
 
 int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const uint8_t *host_mask, int dev,
                    hipStream_t stream, std::shared_ptr<Plan> *out) {
-  const bool hasv = hp->kind != SWIFT_SGDM;
+  const bool hasm = kind_has_m(hp->kind), hasv = kind_has_v(hp->kind);
   const bool bf16 = hp->grad_dtype == SWIFT_BF16;
   const bool hasxb = l->param_bf16 != nullptr;
   // header, then per tensor: numel, mask byte, the pointers (zero for an empty tensor, whose pointers are never read)
-  const size_t per_tensor = 8 + 1 + 8 * (3 + (hasv ? 1 : 0) + (hasxb ? 1 : 0));
+  const size_t per_tensor = 8 + 1 + 8 * (2 + (hasm ? 1 : 0) + (hasv ? 1 : 0) + (hasxb ? 1 : 0));
   std::string key(32 + (size_t)l->n * per_tensor, '\0');
   char *kp = &key[0];
   auto put = [&kp](const auto &v) {
@@ -544,7 +558,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     kp += sizeof v;
   };
   put((uint8_t)'O');
-  put((uint8_t)hasv);
+  put((uint8_t)((hasv ? 1 : 0) | (hasm ? 2 : 0)));
   put((uint8_t)bf16);
   put((uint8_t)hasxb);
   put((int32_t)dev);
@@ -558,7 +572,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     const bool live = n != 0;
     put(live ? (const void *)l->param[i] : nullptr);
     put(live ? l->grad[i] : nullptr);
-    put(live ? (const void *)l->m[i] : nullptr);
+    if (hasm) put(live ? (const void *)l->m[i] : nullptr);
     if (hasv) put(live ? (const void *)l->v[i] : nullptr);
     if (hasxb) put(live ? (const void *)l->param_bf16[i] : nullptr);
   }
@@ -589,14 +603,14 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     int rc;
     if ((rc = check_device_range(l->param[i], n * 4, dev, "param", i))) return rc;
     if ((rc = check_device_range(l->grad[i], n * gsz, dev, "grad", i))) return rc;
-    if ((rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
+    if (hasm && (rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
     if (hasv && (rc = check_device_range(l->v[i], n * 4, dev, "v", i))) return rc;
     if (hasxb && (rc = check_device_range(l->param_bf16[i], n * 2, dev, "param_bf16", i))) return rc;
     if (hasxb) iv.push_back({(uintptr_t)l->param_bf16[i], (uintptr_t)l->param_bf16[i] + n * 2, true});
-    const uintptr_t x = (uintptr_t)l->param[i], g = (uintptr_t)l->grad[i], m = (uintptr_t)l->m[i];
+    const uintptr_t x = (uintptr_t)l->param[i], g = (uintptr_t)l->grad[i];
     iv.push_back({x, x + n * 4, true});
     iv.push_back({g, g + n * gsz, false});
-    iv.push_back({m, m + n * 4, true});
+    if (hasm) iv.push_back({(uintptr_t)l->m[i], (uintptr_t)l->m[i] + n * 4, true});
     if (hasv) iv.push_back({(uintptr_t)l->v[i], (uintptr_t)l->v[i] + n * 4, true});
     if (!host_mask || host_mask[i]) total += n;
   }
@@ -619,7 +633,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
     const uint64_t n = (uint64_t)l->numel[i];
     if (n == 0) continue;
     plan->t_numel[(size_t)i] = n;
-    char *x = static_cast<char *>(l->param[i]), *m = static_cast<char *>(l->m[i]);
+    char *x = static_cast<char *>(l->param[i]), *m = hasm ? static_cast<char *>(l->m[i]) : nullptr;
     char *v = hasv ? static_cast<char *>(l->v[i]) : nullptr;
     const char *g = static_cast<const char *>(l->grad[i]);
     char *xb = hasxb ? static_cast<char *>(l->param_bf16[i]) : nullptr;
@@ -629,7 +643,7 @@ int build_opt_plan(const swift_tensor_list *l, const swift_hparams *hp, const ui
       ChunkDesc d;
       d.x = reinterpret_cast<float *>(x + off * 4);
       d.g = g + off * gsz;
-      d.m = reinterpret_cast<float *>(m + off * 4);
+      d.m = hasm ? reinterpret_cast<float *>(m + off * 4) : nullptr;
       d.v = hasv ? reinterpret_cast<float *>(v + off * 4) : nullptr;
       d.xb = hasxb ? reinterpret_cast<uint16_t *>(xb + off * 2) : nullptr;
       d.pad = 0;
@@ -658,6 +672,7 @@ constexpr size_t kQueueCounterBytes = kQueueMaxCounters * 128;      // tile coun
 
 #define SWIFT_PICK_KIND(KERNEL, U_, B_)                                                                        \
   switch (kind) {                                                                                              \
+    case SWIFT_SGD: return SWIFT_PICK_FLAGS(KERNEL, kSGD, U_, B_);                                             \
     case SWIFT_SGDM: return SWIFT_PICK_FLAGS(KERNEL, kSGDM, U_, B_);                                           \
     case SWIFT_ADAM: return SWIFT_PICK_FLAGS(KERNEL, kADAM, U_, B_);                                           \
     default: return SWIFT_PICK_FLAGS(KERNEL, kADAMW, U_, B_);                                                  \
@@ -902,7 +917,7 @@ expand_chunks_kernel(const ExpandBatch b, ChunkDesc *__restrict__ table, TensorC
     ChunkDesc d;
     d.x = t.x + off;
     d.g = static_cast<const char *>(t.g) + off * b.g_elem_bytes;
-    d.m = t.m + off;
+    d.m = t.m ? t.m + off : nullptr;
     d.v = t.v ? t.v + off : nullptr;
     d.xb = nullptr;
     d.len = (uint32_t)(left < ce ? left : ce);
@@ -950,7 +965,7 @@ int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, cons
   if ((rc = device_info(dev, &info))) return rc;
   void *base = nullptr;
   if ((rc = scratch_for_device(dev, &base))) return rc;
-  const bool bf16 = hp->grad_dtype == SWIFT_BF16, hasv = hp->kind != SWIFT_SGDM;
+  const bool bf16 = hp->grad_dtype == SWIFT_BF16, hasm = kind_has_m(hp->kind), hasv = kind_has_v(hp->kind);
   const size_t gsz = bf16 ? 2 : 4;
   if ((rc = check_device_range(device_mask, (size_t)l->n, dev, "device_mask", 0))) return rc;
   std::lock_guard<std::mutex> lock(g_noalloc_mu);
@@ -960,12 +975,12 @@ int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, cons
     if (n == 0) continue;
     if ((rc = check_device_range(l->param[i], n * 4, dev, "param", i))) return rc;
     if ((rc = check_device_range(l->grad[i], n * gsz, dev, "grad", i))) return rc;
-    if ((rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
+    if (hasm && (rc = check_device_range(l->m[i], n * 4, dev, "m", i))) return rc;
     if (hasv && (rc = check_device_range(l->v[i], n * 4, dev, "v", i))) return rc;
-    const uintptr_t x = (uintptr_t)l->param[i], g = (uintptr_t)l->grad[i], m = (uintptr_t)l->m[i];
+    const uintptr_t x = (uintptr_t)l->param[i], g = (uintptr_t)l->grad[i];
     g_noalloc_iv[n_iv++] = {x, x + n * 4, true};
     g_noalloc_iv[n_iv++] = {g, g + n * gsz, false};
-    g_noalloc_iv[n_iv++] = {m, m + n * 4, true};
+    if (hasm) g_noalloc_iv[n_iv++] = {(uintptr_t)l->m[i], (uintptr_t)l->m[i] + n * 4, true};
     if (hasv) g_noalloc_iv[n_iv++] = {(uintptr_t)l->v[i], (uintptr_t)l->v[i] + n * 4, true};
   }
   if ((rc = check_no_overlap(g_noalloc_iv, n_iv))) return rc;
@@ -999,7 +1014,7 @@ int noalloc_undo_dmask(const swift_tensor_list *l, const swift_hparams *hp, cons
       if (t.numel) {
         t.x = static_cast<float *>(l->param[i]);
         t.g = l->grad[i];
-        t.m = static_cast<float *>(l->m[i]);
+        t.m = hasm ? static_cast<float *>(l->m[i]) : nullptr;
         t.v = hasv ? static_cast<float *>(l->v[i]) : nullptr;
         const uintptr_t bits = (uintptr_t)t.x | (uintptr_t)t.m | (uintptr_t)t.v;
         t.vec_ok = ((bits & 15) == 0) && (((uintptr_t)t.g & (bf16 ? 7 : 15)) == 0);
@@ -1187,6 +1202,7 @@ FusedKernel pick_fused_u(int kind, bool undo, bool bf16, bool xb) {
   (undo ? (bf16 ? SWIFT_PICK2(K, true, true) : SWIFT_PICK2(K, true, false))   \
         : (bf16 ? SWIFT_PICK2(K, false, true) : SWIFT_PICK2(K, false, false)))
   switch (kind) {
+    case SWIFT_SGD: return SWIFT_PICK(kSGD);
     case SWIFT_SGDM: return SWIFT_PICK(kSGDM);
     case SWIFT_ADAM: return SWIFT_PICK(kADAM);
     default: return SWIFT_PICK(kADAMW);
@@ -1219,7 +1235,7 @@ int fused_call(const swift_tensor_list *l, const swift_hparams *hp, const uint8_
       return fail(SWIFT_EINVAL, "tensor %lld has 2^32 elements or more: its digest index would not fit", (long long)i);
   if (!digests) return fail(SWIFT_EINVAL, "digests_device is NULL");
   if ((uintptr_t)digests & 7) return fail(SWIFT_EINVAL, "digests_device is not 8-byte aligned");
-  const uint32_t n_groups = hp->kind == SWIFT_SGDM ? 2 : 3;
+  const uint32_t n_groups = 1u + (kind_has_m(hp->kind) ? 1u : 0u) + (kind_has_v(hp->kind) ? 1u : 0u);   // theta [, m [, v]]
   int dev = -1;
   SWIFT_HIP(hipGetDevice(&dev));
   DeviceInfo info;
@@ -1751,7 +1767,7 @@ int swift_arena_layout(int64_t n, const int64_t *numel, int32_t grad_dtype, int3
   if (n < 0 || n > (int64_t)0x7fffffff || (n > 0 && (!numel || !offsets)))
     return fail(SWIFT_EINVAL, "arena_layout: bad n, numel or offsets");
   if (grad_dtype != SWIFT_F32 && grad_dtype != SWIFT_BF16) return fail(SWIFT_EINVAL, "arena_layout: unknown gradient dtype %d", grad_dtype);
-  const int streams = with_v ? 4 : 3;
+  const int streams = with_v > 0 ? 4 : (with_v == 0 ? 3 : 2);
   int64_t off = 0;
   for (int64_t i = 0; i < n; ++i) {
     if (numel[i] < 0 || numel[i] > kMaxNumel) return fail(SWIFT_EINVAL, "arena_layout: numel[%lld] is negative or beyond 2^40", (long long)i);

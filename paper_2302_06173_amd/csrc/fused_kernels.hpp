@@ -23,8 +23,8 @@ namespace swift {
 
 template <int KIND, bool UNDO, bool XB>
 struct OptDigestOp {       // step or undo of one element + digest contributions of its new words
-  static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
-  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = XB;
+  static constexpr bool kLoadG = true, kHasM = (KIND != kSGD), kHasV = (KIND == kADAM || KIND == kADAMW);
+  static constexpr bool kStoreX = true, kStoreM = kHasM, kStoreV = kHasV, kStoreXB = XB;
   static constexpr bool kPost = true;      // the words are mixed after their stores have been issued
   const OptConsts &c;
   uint32_t base;           // index of the chunk's first element inside its tensor, plus the mixer's K1.hi
@@ -35,7 +35,7 @@ struct OptDigestOp {       // step or undo of one element + digest contributions
   __device__ __forceinline__ void post(uint32_t i, float x, float m, float v) {
     const uint32_t idx = base + i;
     dx += digest_mix_pre(idx, __float_as_uint(x));
-    dm += digest_mix_pre(idx, __float_as_uint(m));
+    if constexpr (kHasM) dm += digest_mix_pre(idx, __float_as_uint(m));
     if constexpr (kHasV) dv += digest_mix_pre(idx, __float_as_uint(v));
   }
 };
@@ -60,7 +60,8 @@ opt_digest_kernel(const ChunkDesc *__restrict__ chunks, uint64_t n_slots, uint32
     process_tile<OptDigestOp<KIND, UNDO, XB>, BF16G, U, BLOCK>(op, d, ti, threadIdx.x);
     // lanes 0, 1, 2 end with the theta, m and v sums and store them side by side
     const uint64_t sum = wave_sum3_u64(op.dx, op.dm, op.dv);
-    if (threadIdx.x < (KIND != kSGDM ? 3u : 2u)) st<false>(tile_digest + 3 * w + threadIdx.x, sum);
+    constexpr uint32_t kGroups = (KIND == kSGD) ? 1u : (KIND == kSGDM ? 2u : 3u);   // theta [, m [, v]]
+    if (threadIdx.x < kGroups) st<false>(tile_digest + 3 * w + threadIdx.x, sum);
   } while ((w += gridDim.x) < n_slots);
 }
 

@@ -54,7 +54,7 @@ __device__ __forceinline__ double wave_sum2_f64(double a, double b) {
 
 // Pass 1 of the step: the moment recurrences (written back) and the running sums for the norms.
 struct LambMomentsOp {
-  static constexpr bool kLoadG = true, kHasV = true, kStoreX = false, kStoreM = true, kStoreV = true, kStoreXB = false;
+  static constexpr bool kLoadG = true, kHasM = true, kHasV = true, kStoreX = false, kStoreM = true, kStoreV = true, kStoreXB = false;
   static constexpr bool kPost = false;
   const OptConsts &c;
   double sx = 0.0, su = 0.0;
@@ -74,7 +74,7 @@ struct LambMomentsOp {
 // Pass 3 of the step: x <- x - (eta q)(r + lambda x), r from the stored new moments.
 template <bool XB>
 struct LambApplyOp {
-  static constexpr bool kLoadG = false, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false, kStoreXB = XB;
+  static constexpr bool kLoadG = false, kHasM = true, kHasV = true, kStoreX = true, kStoreM = false, kStoreV = false, kStoreXB = XB;
   static constexpr bool kPost = false;
   const OptConsts &c;
   double eta_q;

@@ -1,7 +1,7 @@
 // Optimizer step / update-undo kernels for gfx950 (one multi-tensor launch per call).
 //
 // What is computed: Alg. 1 and Alg. 2 of the paper (SGD with momentum and its undo) and the
-// Adam / AdamW pairs of App. A.  How: the tensor list is cut into a flat table of chunks (runs of
+// SGD / Adam / AdamW pairs of App. A.  How: the tensor list is cut into a flat table of chunks (runs of
 // one tensor's elements); one 64-lane workgroup handles one tile of a chunk.  Each lane moves 16
 // bytes per stream (theta, g, m, v in; theta, m, v out), widens to binary64, applies the update
 // lines with explicit FMAs and rounds once on the way out.  The path is HBM-bound (28 bytes per
@@ -13,7 +13,7 @@
 
 namespace swift {
 
-constexpr int kSGDM = 0, kADAM = 1, kADAMW = 2;
+constexpr int kSGDM = 0, kADAM = 1, kADAMW = 2, kSGD = 3;   // kSGD: App. A's plain SGD, no optimizer state
 constexpr int kThreads = 256;           // 4 wavefronts of 64
 // Launch shapes of the optimizer kernels that get compiled: X(U, BLOCK) = 16-byte vectors per lane,
 // lanes per workgroup.  The product builds the measured best only; -DSWIFT_SWEEP_SHAPES adds the
@@ -44,6 +44,9 @@ constexpr int kThreads = 256;           // 4 wavefronts of 64
 #endif
 #ifndef SWIFT_DEFAULT_WAVES_PER_CU_SGDM
 #define SWIFT_DEFAULT_WAVES_PER_CU_SGDM 14
+#endif
+#ifndef SWIFT_DEFAULT_WAVES_PER_CU_SGD
+#define SWIFT_DEFAULT_WAVES_PER_CU_SGD 24   // plain SGD: 2 streams in, 1 out (7B list: 6.34 TB/s at 14, 6.73 at 18, 6.82 at 24, 6.72 at 28)
 #endif
 #ifndef SWIFT_FUSED_U
 #define SWIFT_FUSED_U 1                 // step/undo fused with the digest: vectors per lane
@@ -92,8 +95,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct ChunkDesc {         // one per chunk of the optimizer kernels, 64 bytes, device resident
   float *x;                // theta of the chunk's first element, in/out
   const void *g;           // gradient, fp32 or bf16, read only
-  float *m;                // momentum buffer / first moment, in/out
-  float *v;                // second moment, in/out (null for SGDM)
+  float *m;                // momentum buffer / first moment, in/out (null for plain SGD)
+  float *v;                // second moment, in/out (null for SGDM and plain SGD)
   uint16_t *xb;            // bfloat16 copy of theta, out only (null if the caller keeps none)
   uint32_t len;            // elements in this chunk (the last chunk of a tensor is short)
   uint32_t tensor;         // index of the tensor in the caller's list (for the device mask)
@@ -191,7 +194,10 @@ __device__ __forceinline__ double sqrt_moment(double x) {
 template <int KIND, bool UNDO>
 __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, float &vf, const OptConsts &c) {
   const double x = (double)xf, g = (double)gf, m = (double)mf;
-  if constexpr (KIND == kSGDM) {
+  if constexpr (KIND == kSGD) {                     // App. A "SGD" / "Undo SGD": theta only
+    if constexpr (!UNDO) xf = (float)fma(-c.eta, fma(c.lam, x, g), x);
+    else xf = (float)(fma(c.eta, g, x) * c.inv_oml);
+  } else if constexpr (KIND == kSGDM) {
     if constexpr (!UNDO) {                          // Alg. 1
       const double gp = fma(c.lam, x, g);
       const double mt = fma(c.mu, m, c.omt * gp);
@@ -234,7 +240,7 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
 }
 
 // An "op" tells process_tile which streams a kernel moves and what to do with one element:
-//   kLoadG, kHasV          gradient / second moment are read
+//   kLoadG, kHasM, kHasV   gradient / first moment (momentum buffer) / second moment are read
 //   kStoreX, kStoreM, kStoreV   streams written back
 //   kStoreXB               the bfloat16 copy of the new theta is written too
 //   elem(i, x, g, m, v)    the arithmetic of element i of the chunk (may also accumulate into
@@ -244,8 +250,8 @@ __device__ __forceinline__ void update_elem(float &xf, float gf, float &mf, floa
 //                          while the stores are on their way)
 template <int KIND, bool UNDO, bool XB = false>
 struct OptOp {             // optimizer step or undo of one element
-  static constexpr bool kLoadG = true, kHasV = (KIND != kSGDM);
-  static constexpr bool kStoreX = true, kStoreM = true, kStoreV = kHasV, kStoreXB = XB;
+  static constexpr bool kLoadG = true, kHasM = (KIND != kSGD), kHasV = (KIND == kADAM || KIND == kADAMW);
+  static constexpr bool kStoreX = true, kStoreM = kHasM, kStoreV = kHasV, kStoreXB = XB;
   static constexpr bool kPost = false;
   const OptConsts &c;
   __device__ __forceinline__ void elem(uint32_t, float &x, float g, float &m, float &v) {
@@ -257,10 +263,10 @@ template <typename Op>
 __device__ __forceinline__ void update_vec4(Op &op, uint32_t j, f32x4 &x, const f32x4 &g, f32x4 &m, f32x4 &v) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    float xe = x[k], me = m[k], ve = Op::kHasV ? v[k] : 0.f;
+    float xe = x[k], me = Op::kHasM ? m[k] : 0.f, ve = Op::kHasV ? v[k] : 0.f;
     op.elem(4u * j + k, xe, Op::kLoadG ? g[k] : 0.f, me, ve);
     x[k] = xe;
-    m[k] = me;
+    if constexpr (Op::kHasM) m[k] = me;
     if constexpr (Op::kHasV) v[k] = ve;
   }
 }
@@ -268,7 +274,7 @@ __device__ __forceinline__ void update_vec4(Op &op, uint32_t j, f32x4 &x, const 
 template <typename Op>
 __device__ __forceinline__ void post_vec4(Op &op, uint32_t j, const f32x4 &x, const f32x4 &m, const f32x4 &v) {
 #pragma unroll
-  for (int k = 0; k < 4; ++k) op.post(4u * j + k, x[k], m[k], Op::kHasV ? v[k] : 0.f);
+  for (int k = 0; k < 4; ++k) op.post(4u * j + k, x[k], Op::kHasM ? m[k] : 0.f, Op::kHasV ? v[k] : 0.f);
 }
 
 // The bfloat16 copy of vector j (4 consecutive elements): 8 bytes.
@@ -304,7 +310,8 @@ __device__ __forceinline__ float load_grad1(const void *g, int64_t i) {
 // One element through 4-byte accesses (ragged tails and unaligned tensors).
 template <typename Op, bool BF16G>
 __device__ __forceinline__ void process_scalar(Op &op, const ChunkDesc &d, uint32_t e) {
-  float xe = ld<false>(d.x + e), me = ld<false>(d.m + e), ve = 0.f, ge = 0.f;
+  float xe = ld<false>(d.x + e), me = 0.f, ve = 0.f, ge = 0.f;
+  if constexpr (Op::kHasM) me = ld<false>(d.m + e);
   if constexpr (Op::kHasV) ve = ld<false>(d.v + e);
   if constexpr (Op::kLoadG) ge = load_grad1<BF16G>(d.g, e);
   op.elem(e, xe, ge, me, ve);
@@ -324,13 +331,14 @@ struct NoHook {
 // ti * U*BLOCK*4 of the chunk (the caller has checked that this is inside the chunk).
 template <typename Op, bool BF16G, int U, int BLOCK, typename Hook = NoHook>
 __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_t ti, uint32_t tid, Hook hook = Hook()) {
-  constexpr bool HASV = Op::kHasV;
+  constexpr bool HASV = Op::kHasV, HASM = Op::kHasM;
+  const f32x4 zero4{0.f, 0.f, 0.f, 0.f};
   constexpr uint32_t TILE4 = U * BLOCK;                          // vectors per tile
   const uint32_t len = d.len;
   if (d.vec_ok) {
     // chunk starts are multiples of 4 elements, so chunks keep their tensor's 16-byte alignment
     const uint32_t n4 = len >> 2;
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(d.x, n4 * 16u), rm = make_rsrc(d.m, n4 * 16u);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(d.x, n4 * 16u), rm = make_rsrc(d.m, HASM ? n4 * 16u : 0u);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc(d.v, HASV ? n4 * 16u : 0u);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc(d.g, Op::kLoadG ? n4 * (BF16G ? 8u : 16u) : 0u);
     const __amdgpu_buffer_rsrc_t rxb = make_rsrc(d.xb, Op::kStoreXB ? n4 * 8u : 0u);
@@ -341,9 +349,9 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
       for (int u = 0; u < U; ++u) {
         const uint32_t j = j0 + u * BLOCK + tid;
         xr[u] = buf_ld4(rx, j * 16u);
-        gr[u] = Op::kLoadG ? load_grad4<BF16G>(rg, j) : f32x4{0.f, 0.f, 0.f, 0.f};
-        mr[u] = buf_ld4(rm, j * 16u);
-        vr[u] = HASV ? buf_ld4(rv, j * 16u) : f32x4{0.f, 0.f, 0.f, 0.f};
+        gr[u] = Op::kLoadG ? load_grad4<BF16G>(rg, j) : zero4;
+        mr[u] = HASM ? buf_ld4(rm, j * 16u) : zero4;
+        vr[u] = HASV ? buf_ld4(rv, j * 16u) : zero4;
       }
       // Every load of the tile goes out before anything waits for one of them.  Left alone, the scheduler put the
       // last load of the undo kernels with bf16 gradients behind the wait for the first (a full memory latency per
@@ -366,9 +374,9 @@ __device__ __forceinline__ void process_tile(Op &op, const ChunkDesc &d, uint32_
     } else {                                                     // ragged end of a tensor
       hook.after_loads();
       for (uint32_t j = j0 + tid; j < n4; j += BLOCK) {
-        f32x4 xr = buf_ld4(rx, j * 16u), mr = buf_ld4(rm, j * 16u);
-        f32x4 gr = Op::kLoadG ? load_grad4<BF16G>(rg, j) : f32x4{0.f, 0.f, 0.f, 0.f};
-        f32x4 vr = HASV ? buf_ld4(rv, j * 16u) : f32x4{0.f, 0.f, 0.f, 0.f};
+        f32x4 xr = buf_ld4(rx, j * 16u), mr = HASM ? buf_ld4(rm, j * 16u) : zero4;
+        f32x4 gr = Op::kLoadG ? load_grad4<BF16G>(rg, j) : zero4;
+        f32x4 vr = HASV ? buf_ld4(rv, j * 16u) : zero4;
         update_vec4(op, j, xr, gr, mr, vr);
         if constexpr (Op::kStoreX) buf_st4(rx, j * 16u, xr);
         if constexpr (Op::kStoreXB) buf_st_bf16x4(rxb, j, xr);

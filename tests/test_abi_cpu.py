@@ -89,7 +89,8 @@ def test_hyper_parameter_domain(B, fn):
 def test_not_invertible_is_an_undo_only_error(B):
     for hp in (B.hparams("adam", step=1, lr=0.1, beta1=0.0),
                B.hparams("adamw", step=1, lr=0.1, beta2=0.0),
-               B.hparams("adamw", step=1, lr=0.5, weight_decay=2.0)):
+               B.hparams("adamw", step=1, lr=0.5, weight_decay=2.0),
+               B.hparams("sgd", step=1, lr=0.5, weight_decay=2.0)):       # App. A "Undo SGD" divides by 1 - eta lambda
         assert _call(B, "swift_opt_undo", hp) == B.SWIFT_ENOTINVERTIBLE
         assert "divides" in B.swift_last_error()
         assert _call(B, "swift_opt_step", hp) == B.SWIFT_OK
@@ -258,6 +259,9 @@ def test_arena_layout_is_host_arithmetic_and_matches_the_benchmark_state(B):
                 if nbytes >= 1 << 20:
                     assert (off - o) % 4096 == 2048            # an odd multiple of 2 KiB to the next buffer
         assert total == off
+    rows, total = B.swift_arena_layout([1 << 18, 5], with_v=False, with_m=False)      # plain SGD: theta and g only
+    assert [len(r) for r in rows] == [2, 2] and rows[0] == [0, synth.padded_extent(4 << 18)]
+    assert total == 2 * synth.padded_extent(4 << 18) + 2 * 256
     assert B.swift_arena_layout([], with_v=True) == ([], 0)
     with pytest.raises(B.SwiftError):
         B.swift_arena_layout([-1])
