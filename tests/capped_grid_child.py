@@ -31,10 +31,10 @@ def run(out_path: str) -> None:
             res[f"{tag}_m{k}"] = b.cpu().numpy()
             res[f"{tag}_v{k}"] = c.cpu().numpy()
 
-    for kind in ("sgdm", "adam", "adamw"):
+    for kind in ("sgd", "sgdm", "adam", "adamw"):
         th, g, m, v = state()
         hp = B.hparams(kind, step=7, lr=1e-3, weight_decay=0.01, momentum=0.9, beta1=0.9, beta2=0.999)
-        tl = B.TensorList(th, g, m, None if kind == "sgdm" else v)
+        tl = B.TensorList(th, g, None if kind == "sgd" else m, v if kind in ("adam", "adamw") else None)
         B.swift_opt_step(tl, hp)
         keep(kind + "_step", th, m, v)
         B.swift_opt_undo(tl, hp)
