@@ -304,7 +304,8 @@ int swift_stream_copy(void *dst_device, const void *src_device, int64_t bytes, v
  * checkpoint_interval: T > 0 iterations.  bandwidth: B > 0 bytes per time unit of R (infinity allowed).
  * group_of: HOST, n_machines entries out: group index of each machine, groups numbered from 0 in
  * pipeline order.  storage_out / recovery_out (nullable): T * bytes on the remaining inter-group links,
- * and the expected recovery time sum_G R(G)|G|/N of the result.  O(n_machines^2) time. */
+ * and the expected recovery time sum_G R(G)|G|/N of the result.  O(n_machines log n_machines) time: the result is
+ * that of the paper's loop, found with a priority queue instead of a scan per merge. */
 int swift_logging_groups(int64_t n_machines, const double *compute_time, const double *message_bytes,
                          double checkpoint_interval, double bandwidth, double storage_limit, int parallel_recovery,
                          int32_t *group_of, double *storage_out, double *recovery_out);

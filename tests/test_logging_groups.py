@@ -51,6 +51,37 @@ def test_same_groups_as_the_oracle_on_random_pipelines(B, parallel):
             assert s == pytest.approx(storage, rel=1e-13, abs=1e-6) and e == pytest.approx(recovery, rel=1e-13)
 
 
+def test_limits_that_sit_exactly_on_a_storage_value(B):
+    """The loop ends when T * sum(M) <= limit.  Limits equal to the storage of an intermediate grouping, one ulp to
+    either side of it, below zero, zero and infinite: the library (which keeps a running sum and re-forms the
+    in-order sum only near the limit) must stop exactly where the oracle's in-order sum stops, and report that sum."""
+    rng = random.Random(5)
+    for trial in range(120):
+        n = rng.randint(2, 40)
+        R = [rng.uniform(0.5, 2) for _ in range(n)]
+        M = [rng.choice([0.0, rng.uniform(1, 100), float(rng.randint(1, 9))]) for _ in range(n - 1)]
+        T, Bw = rng.choice([1.0, 3.0, 100.0]), rng.choice([1e3, math.inf])
+        _, st, _, _ = group_machines(R, M, T, Bw, rng.uniform(0, T * sum(M)), rng.random() < 0.5)
+        for parallel in (False, True):
+            for limit in (st, math.nextafter(st, -math.inf), math.nextafter(st, math.inf), -1.0, 0.0, math.inf):
+                groups, storage, recovery, _ = group_machines(R, M, T, Bw, limit, parallel)
+                got, s, e = B.swift_logging_groups(R, M, T, Bw, limit, parallel)
+                assert got == _group_of(groups), (trial, limit, parallel)
+                assert s == storage and e == pytest.approx(recovery, rel=1e-13)
+
+
+def test_long_pipelines_take_milliseconds(B):
+    rng = random.Random(9)
+    n = 16384
+    R = [rng.uniform(0.5, 2.0) for _ in range(n)]
+    M = [rng.uniform(1e6, 1e8) for _ in range(n - 1)]
+    t0 = time.perf_counter()
+    got, s, _ = B.swift_logging_groups(R, M, 100.0, 1e9, 0.05 * 100.0 * sum(M), False)
+    assert time.perf_counter() - t0 < 2.0                       # (a scan per merge takes about a second here)
+    assert s <= 0.05 * 100.0 * sum(M) and got[0] == 0 and got[-1] == max(got)
+    assert all(b - a in (0, 1) for a, b in zip(got, got[1:]))   # groups are runs of adjacent machines, numbered in order
+
+
 def test_identical_inputs_tie_to_the_lowest_index(B):
     got, _, _ = B.swift_logging_groups([1.0] * 8, [5.0] * 7, 1.0, math.inf, 15.0)
     assert got == [0, 0, 1, 1, 2, 2, 3, 3]
